@@ -1,0 +1,190 @@
+/*
+ * moe_mpmc.h -- C ABI of the MI355X (gfx950) library for the Switch-style top-1 MoE layer
+ * forward with predictor-driven dynamic expert replication.
+ *
+ * The calls follow the data flow of the paper's two algorithms: the hash-building thread
+ * (Algorithm 2) predicts an expert id per token (sru_predict); the inference thread
+ * (Algorithm 1) turns the predicted ids into per-expert replica counts within a cap
+ * (replica_plan), re-points tokens to physical replicas (moe_dispatch) and runs the
+ * specialised model (moe_route for the gate, moe_expert_ffn, moe_combine).
+ *
+ * Conventions (all calls)
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller, row-major, contiguous,
+ *    16-byte aligned.  The library never allocates, frees or keeps device memory; scratch
+ *    space is a caller-supplied workspace whose size the *_workspace_bytes functions give.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *    kernels and return without synchronising.  Data-dependent sizes (rows kept, slot
+ *    ranges) stay in device memory; grids are sized for the worst case.
+ *  - dtype: MOE_F32 = binary32 tensors; MOE_BF16 = bfloat16 tensors, products accumulated
+ *    in binary32.  Index tensors are int32, probabilities binary32.
+ *  - Return value: MOE_OK or a negative error code.  Arguments are validated on the host
+ *    before anything is launched; on error nothing has been enqueued (MOE_ERR_HIP excepted).
+ *    moe_last_error() returns a thread-local message for the last failing call.
+ *  - No C++ exception crosses the boundary.  Calls on different streams may overlap only if
+ *    they use different workspaces and outputs.
+ */
+#ifndef MOE_MPMC_H
+#define MOE_MPMC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_OK 0
+#define MOE_ERR_INVALID_ARG (-1) /* null pointer, negative size, misaligned shape          */
+#define MOE_ERR_UNSUPPORTED (-2) /* dtype / shape / layout outside the built kernels       */
+#define MOE_ERR_WORKSPACE (-3)   /* workspace missing or smaller than *_workspace_bytes    */
+#define MOE_ERR_HIP (-4)         /* the HIP runtime refused a launch                       */
+
+#define MOE_F32 0
+#define MOE_BF16 1
+
+#define MOE_MAX_EXPERTS 1024 /* E  <= 1024 */
+#define MOE_MAX_SLOTS 4096   /* E + replica budget <= 4096 */
+
+#define MOE_LAYOUT_PLAIN 0  /* [E, K, N] row-major                                        */
+#define MOE_LAYOUT_PACKED 1 /* image written by moe_pack_weights                          */
+
+#define MOE_SCHEDULE_SLOTS 0   /* one stream of row tiles per physical slot (replication on) */
+#define MOE_SCHEDULE_EXPERTS 1 /* one work item per logical expert walks all its rows        */
+
+const char *moe_last_error(void);
+int moe_version(void);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_route -- the softmax gate of the top-1 layer (Methodology: "a model similar to
+ * SwitchTransformers (top-1)"; Preliminaries: routing via softmax).
+ *   logit[s][e] = sum_k x[s][k] * w_router[k][e] + b_router[e]
+ *   expert_idx[s]  = argmax_e logit[s][e]          (lowest e on an exact tie)
+ *   expert_prob[s] = softmax(logit[s])[expert_idx[s]]
+ * x [T,d]; w_router [d,E]; b_router [E] binary32 or NULL (= 0); logits_opt [T,E] binary32
+ * or NULL.  Sums, exponentials and the argmax are taken in binary32 for both dtypes.
+ * d must be a multiple of 8.  T = 0 is a no-op.
+ */
+size_t moe_route_workspace_bytes(int T, int d, int E, int dtype);
+int moe_route(const void *x, const void *w_router, const float *b_router, int T, int d, int E,
+              int dtype, int32_t *expert_idx, float *expert_prob, float *logits_opt, void *ws,
+              size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * sru_predict -- the expert predictor h_l of Algorithm 2 ("Expert k <- h_l(X_i[s])"): a stack
+ * of SRU layers (equations of the subsection "Simple Recurrent Unit (SRU) for expert
+ * prediction") followed by a linear head and an argmax.
+ *   per layer and sequence, t = 0..L-1, c_{-1} = 0:
+ *     x' = W x_t;  f = sigmoid(W_f x_t + b_f);  r = sigmoid(W_r x_t + b_r)
+ *     c_t = f*c_{t-1} + (1-f)*x';   h_t = r*tanh(c_t) + (1-r)*hw_t
+ *     hw_t = x_t when the layer's input width equals n_hidden, else W_h x_t
+ *   logits = h_last W_head + b_head;  pred_idx = argmax (lowest index on a tie)
+ * The struct and every array it points to live in HOST memory; the weight tensors they name
+ * are device pointers.  w_cat[l] is [n_in_l, k_l*n_hidden], column blocks W | W_f | W_r and,
+ * when n_in_l != n_hidden (k_l = 4), W_h; n_in_0 = n_in, n_in_l = n_hidden afterwards.
+ * b_f / b_r: arrays of n_layers device pointers to [n_hidden] binary32, or NULL (all zero);
+ * single entries may be NULL too.  w_head [n_hidden, n_out]; b_head [n_out] or NULL.
+ * emb [B, L, n_in].  Only MOE_BF16 is built; n_in and n_hidden multiples of 64, n_out a
+ * multiple of 128 and <= 256.  Layer outputs are stored as bfloat16 between layers.
+ */
+typedef struct sru_weights {
+    int n_layers, n_in, n_hidden, n_out;
+    const void *const *w_cat;
+    const float *const *b_f;
+    const float *const *b_r;
+    const void *w_head;
+    const float *b_head;
+} sru_weights;
+
+size_t sru_predict_workspace_bytes(const sru_weights *w, int B, int L, int dtype);
+int sru_predict(const void *emb, const sru_weights *w, int B, int L, int dtype, int32_t *pred_idx,
+                float *logits_opt /* [B*L, n_out] or NULL */, void *ws, size_t ws_bytes,
+                void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * replica_plan -- Algorithm 1's replication pass under the cap of the subsection "Capacity
+ * capping".  From the ids idx[T] (predicted, or the router's own):
+ *   n_e = #{s : idx[s] = e};  every expert owns one slot;
+ *   want_e = max(0, ceil(n_e / slot_capacity) - 1) further replicas (slot_capacity = 1 is the
+ *   algorithm as printed: one replica per further token);  D = sum want_e;
+ *   D <= budget : replicas[e] = 1 + want_e;
+ *   otherwise the budget is divided by the number of replicas still to be added:
+ *     policy 0: replicas[e] = 1 + floor(budget*want_e / D), and the slots the floors leave
+ *               go one by one to the expert with the largest n_e / replicas[e] among those
+ *               still below 1 + want_e (lowest id on a tie);
+ *     policy 1: equal shares among the experts that still want replicas, repeated until the
+ *               share is 0, the remainder as in policy 0.
+ * Outputs: plan_counts[E] = n_e; replicas[E]; slot_base[E+1] = exclusive scan of replicas;
+ * slot_expert[E+budget] (slot -> expert, expert-major; unused tail = -1); n_slots[1].
+ * Integer-only; ids outside [0,E) are ignored.  E <= MOE_MAX_EXPERTS, E+budget <=
+ * MOE_MAX_SLOTS.
+ */
+int replica_plan(const int32_t *idx, int T, int E, int budget, int slot_capacity, int policy,
+                 int32_t *plan_counts, int32_t *replicas, int32_t *slot_base,
+                 int32_t *slot_expert, int32_t *n_slots, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_dispatch -- capacity-limited dispatch of tokens to physical slots (Algorithm 1: a token
+ * is re-pointed to a replica index; the inference-thread subsection: tokens are processed in
+ * parallel while the batch stays within the capacity of the experts on the GPU).
+ *   counts[e] = n_e (actual ids);  kept[e] = min(n_e, replicas[e]*slot_capacity);
+ *   expert_offset[E+1] = exclusive scan of kept;  K = expert_offset[E];
+ *   j(s) = rank of s among earlier tokens of its expert; kept iff j(s) < replicas[e]*C;
+ *   inv[s] = expert_offset[e] + j(s) or -1;  perm[inv[s]] = s;  perm[K..T) = -1;
+ *   x_perm[inv[s]] = x[s];  rows K..T of x_perm are left untouched;
+ *   slot k of expert e covers q + (k < rem) consecutive rows (q, rem = kept[e] div/mod
+ *   replicas[e]); slot_offset[max_slots+1] holds the first row of every slot, expert-major,
+ *   entries from sum(replicas) on hold K.
+ * replicas may be NULL (one slot per expert).  d*sizeof(element) must be a multiple of 16.
+ * Ids must lie in [0,E).  Deterministic: no result depends on atomics order.
+ */
+size_t moe_dispatch_workspace_bytes(int T, int E);
+int moe_dispatch(const void *x, const int32_t *expert_idx, const int32_t *replicas, int T, int d,
+                 int E, int slot_capacity, int max_slots, int dtype, int32_t *counts,
+                 int32_t *kept, int32_t *expert_offset, int32_t *slot_offset, int32_t *perm,
+                 int32_t *inv, void *x_perm, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_pack_weights -- one-time re-layout of static expert weights for the bf16 matrix-core
+ * kernels (inference weights do not change between batches).  Input w [E, K, N] row-major
+ * bf16; output element ((e*(K/8) + k/8)*N + n)*8 + k%8 = w[e][k][n].  K a multiple of 8.
+ * moe_packed_weights_bytes gives the output size (equal to the input size).
+ */
+size_t moe_packed_weights_bytes(int E, int K, int N, int dtype);
+int moe_pack_weights(const void *w, int E, int K, int N, int dtype, void *w_packed, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_expert_ffn -- the experts and their replicas process their tokens concurrently
+ * (Abstract; contribution 2).  For every slot p < n_slots[0], e = slot_expert[p], rows
+ * slot_offset[p] .. slot_offset[p+1]-1 of x_perm:
+ *   h = relu(x_perm[row] W1[e])  (stored in dtype),   y_perm[row] = h W2[e]  (stored in dtype)
+ * W1 [E,d,F], W2 [E,F,d].  MOE_F32 takes MOE_LAYOUT_PLAIN; MOE_BF16 takes MOE_LAYOUT_PACKED
+ * (each of W1, W2 packed with moe_pack_weights, K = d resp. F) and needs d % 128 == 0,
+ * F % 128 == 0.  schedule: MOE_SCHEDULE_SLOTS gives every slot its own row tiles, so the
+ * replicas of a hot expert run side by side; MOE_SCHEDULE_EXPERTS makes one work item per
+ * (expert, column tile) walk all rows of that expert one tile after another (tokens queue on
+ * the one physical expert).  Both produce the same y_perm.  max_rows bounds the rows
+ * (normally T), max_slots the slot tables, E the expert count of W1/W2 (slots naming an
+ * expert outside [0,E) are skipped).  Rows outside all slots are not written.
+ */
+size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, int d, int F, int dtype);
+int moe_expert_ffn(const void *x_perm, const void *w1, const void *w2, int weight_layout,
+                   const int32_t *slot_offset, const int32_t *slot_expert, const int32_t *n_slots,
+                   int max_rows, int max_slots, int E, int d, int F, int dtype, int schedule,
+                   void *y_perm, void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * moe_combine -- expert output scaled by the gate probability, back in token order; tokens
+ * over capacity pass through unchanged (the replicated model keeps the baseline layer's
+ * computation: Preliminaries, Conclusion).
+ *   inv[s] >= 0 : out[s] = (residual ? x[s] : 0) + expert_prob[s] * y_perm[inv[s]]
+ *                 (binary32 multiply-add, rounded once to dtype)
+ *   inv[s] <  0 : out[s] = x[s]  bit for bit
+ * out must not alias x or y_perm.  d*sizeof(element) a multiple of 16.
+ */
+int moe_combine(const void *y_perm, const void *x, const int32_t *inv, const float *expert_prob,
+                int T, int d, int dtype, int residual, void *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_MPMC_H */

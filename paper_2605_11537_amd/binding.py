@@ -1,0 +1,257 @@
+"""ctypes binding of ``libmoe_mpmc.so``: the same six calls (plus weight packing) on torch
+tensors.  Argument marshalling only -- every step of the path runs in the HIP kernels.  Torch
+is used for device memory and the current stream, nothing else.  There is no CPU fallback:
+if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+MOE_F32, MOE_BF16 = 0, 1
+LAYOUT_PLAIN, LAYOUT_PACKED = 0, 1
+SCHEDULE_SLOTS, SCHEDULE_EXPERTS = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_mpmc.so")
+_lib = None
+
+EXPORTS = (
+    "moe_last_error", "moe_version",
+    "moe_route_workspace_bytes", "moe_route",
+    "sru_predict_workspace_bytes", "sru_predict",
+    "replica_plan",
+    "moe_dispatch_workspace_bytes", "moe_dispatch",
+    "moe_packed_weights_bytes", "moe_pack_weights",
+    "moe_expert_ffn_workspace_bytes", "moe_expert_ffn",
+    "moe_combine",
+)
+
+
+class MoeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"[{code}] {msg}")
+        self.code = code
+
+
+class SruWeightsC(C.Structure):
+    _fields_ = [("n_layers", C.c_int), ("n_in", C.c_int), ("n_hidden", C.c_int), ("n_out", C.c_int),
+                ("w_cat", C.POINTER(C.c_void_p)), ("b_f", C.POINTER(C.c_void_p)),
+                ("b_r", C.POINTER(C.c_void_p)), ("w_head", C.c_void_p), ("b_head", C.c_void_p)]
+
+
+def lib():
+    """Load the built library (build it first if it was never built); fail loudly otherwise."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from .build import build_library
+            build_library()
+        _lib = C.CDLL(LIB_PATH)
+        _lib.moe_last_error.restype = C.c_char_p
+        for n in EXPORTS:
+            f = getattr(_lib, n)
+            if n.endswith("_bytes"):
+                f.restype = C.c_size_t
+            elif n != "moe_last_error":
+                f.restype = C.c_int
+        I, S, P = C.c_int, C.c_size_t, C.c_void_p
+        _lib.moe_route_workspace_bytes.argtypes = [I, I, I, I]
+        _lib.moe_route.argtypes = [P, P, P, I, I, I, I, P, P, P, P, S, P]
+        _lib.sru_predict_workspace_bytes.argtypes = [C.POINTER(SruWeightsC), I, I, I]
+        _lib.sru_predict.argtypes = [P, C.POINTER(SruWeightsC), I, I, I, P, P, P, S, P]
+        _lib.replica_plan.argtypes = [P, I, I, I, I, I, P, P, P, P, P, P]
+        _lib.moe_dispatch_workspace_bytes.argtypes = [I, I]
+        _lib.moe_dispatch.argtypes = [P, P, P, I, I, I, I, I, I, P, P, P, P, P, P, P, P, S, P]
+        _lib.moe_packed_weights_bytes.argtypes = [I, I, I, I]
+        _lib.moe_pack_weights.argtypes = [P, I, I, I, I, P, P]
+        _lib.moe_expert_ffn_workspace_bytes.argtypes = [I, I, I, I, I]
+        _lib.moe_expert_ffn.argtypes = [P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P]
+        _lib.moe_combine.argtypes = [P, P, P, P, I, I, I, I, P, P]
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise MoeError(rc, lib().moe_last_error().decode())
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MOE_F32
+    if t.dtype == torch.bfloat16:
+        return MOE_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _i32(n, dev):
+    return torch.empty(n, dtype=torch.int32, device=dev)
+
+
+def _ws(nbytes, dev):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=dev)
+
+
+# --------------------------------------------------------------------------- the calls
+def moe_route(x, w_router, b_router=None, want_logits=False, out=None, ws=None):
+    """-> (expert_idx int32[T], expert_prob f32[T], logits f32[T,E] or None)."""
+    T, d = x.shape
+    E = w_router.shape[1]
+    dev = x.device
+    dt = _dt(x)
+    assert _dt(w_router) == dt and w_router.shape[0] == d
+    idx, prob = out if out is not None else (_i32(T, dev), torch.empty(T, dtype=torch.float32, device=dev))
+    logits = torch.empty(T, E, dtype=torch.float32, device=dev) if want_logits else None
+    need = lib().moe_route_workspace_bytes(T, d, E, dt)
+    ws = ws if ws is not None else _ws(need, dev)
+    _check(lib().moe_route(_ptr(x), _ptr(w_router), _ptr(b_router), T, d, E, dt, _ptr(idx), _ptr(prob),
+                           _ptr(logits), _ptr(ws), ws.numel(), _stream()))
+    return idx, prob, logits
+
+
+class SruWeights:
+    """Holds the device tensors of an SRU predictor and the host-side C struct naming them."""
+
+    def __init__(self, w_cat, b_f, b_r, w_head, b_head=None):
+        self.tensors = (list(w_cat), list(b_f) if b_f else None, list(b_r) if b_r else None, w_head, b_head)
+        n = len(w_cat)
+        self.n_layers = n
+        self.n_in = w_cat[0].shape[0]
+        self.n_hidden, self.n_out = w_head.shape
+        PT = C.c_void_p * n
+        self._wc = PT(*[w.data_ptr() for w in w_cat])
+        self._bf = PT(*[(b.data_ptr() if b is not None else None) for b in b_f]) if b_f else None
+        self._br = PT(*[(b.data_ptr() if b is not None else None) for b in b_r]) if b_r else None
+        self.c = SruWeightsC(n, self.n_in, self.n_hidden, self.n_out,
+                             C.cast(self._wc, C.POINTER(C.c_void_p)),
+                             C.cast(self._bf, C.POINTER(C.c_void_p)) if self._bf else None,
+                             C.cast(self._br, C.POINTER(C.c_void_p)) if self._br else None,
+                             w_head.data_ptr(), b_head.data_ptr() if b_head is not None else None)
+
+
+def sru_predict(emb, weights: SruWeights, want_logits=False, out=None, ws=None):
+    """emb [B,L,n_in] -> (pred_idx int32[B*L], logits f32[B*L,n_out] or None)."""
+    B, L, _ = emb.shape
+    dev = emb.device
+    dt = _dt(emb)
+    pred = out if out is not None else _i32(B * L, dev)
+    logits = torch.empty(B * L, weights.n_out, dtype=torch.float32, device=dev) if want_logits else None
+    if ws is None:
+        need = lib().sru_predict_workspace_bytes(C.byref(weights.c), B, L, dt)
+        if need == 0:
+            _check(lib().sru_predict(None, C.byref(weights.c), B, L, dt, None, None, None, 0, None) or -2)
+        ws = _ws(need, dev)
+    _check(lib().sru_predict(_ptr(emb), C.byref(weights.c), B, L, dt, _ptr(pred), _ptr(logits), _ptr(ws),
+                             ws.numel(), _stream()))
+    return pred, logits
+
+
+def replica_plan(idx, E, budget, slot_capacity, policy=0, out=None):
+    """-> dict(plan_counts[E], replicas[E], slot_base[E+1], slot_expert[E+budget], n_slots[1])."""
+    dev = idx.device
+    o = out if out is not None else dict(plan_counts=_i32(E, dev), replicas=_i32(E, dev),
+                                         slot_base=_i32(E + 1, dev), slot_expert=_i32(E + budget, dev),
+                                         n_slots=_i32(1, dev))
+    _check(lib().replica_plan(_ptr(idx), idx.shape[0], E, budget, slot_capacity, policy, _ptr(o["plan_counts"]),
+                              _ptr(o["replicas"]), _ptr(o["slot_base"]), _ptr(o["slot_expert"]),
+                              _ptr(o["n_slots"]), _stream()))
+    return o
+
+
+def moe_dispatch(x, expert_idx, replicas, E, slot_capacity, max_slots, out=None, ws=None):
+    """-> dict(counts, kept, expert_offset, slot_offset, perm, inv, x_perm)."""
+    T, d = x.shape
+    dev = x.device
+    o = out if out is not None else dict(counts=_i32(E, dev), kept=_i32(E, dev), expert_offset=_i32(E + 1, dev),
+                                         slot_offset=_i32(max_slots + 1, dev), perm=_i32(T, dev),
+                                         inv=_i32(T, dev), x_perm=torch.empty_like(x))
+    ws = ws if ws is not None else _ws(lib().moe_dispatch_workspace_bytes(T, E), dev)
+    _check(lib().moe_dispatch(_ptr(x), _ptr(expert_idx), _ptr(replicas), T, d, E, slot_capacity, max_slots, _dt(x),
+                              _ptr(o["counts"]), _ptr(o["kept"]), _ptr(o["expert_offset"]), _ptr(o["slot_offset"]),
+                              _ptr(o["perm"]), _ptr(o["inv"]), _ptr(o["x_perm"]), _ptr(ws), ws.numel(), _stream()))
+    return o
+
+
+def moe_pack_weights(w, out=None):
+    """[E,K,N] bf16 row-major -> packed image for the matrix-core kernels (same byte size)."""
+    E, K, N = w.shape
+    out = out if out is not None else torch.empty_like(w)
+    _check(lib().moe_pack_weights(_ptr(w), E, K, N, _dt(w), _ptr(out), _stream()))
+    return out
+
+
+def moe_expert_ffn(x_perm, w1, w2, slot_offset, slot_expert, n_slots, E, F, max_slots=None,
+                   schedule=SCHEDULE_SLOTS, weight_layout=None, out=None, ws=None):
+    """-> y_perm [max_rows, d].  bf16 weights must already be packed (``moe_pack_weights``)."""
+    max_rows, d = x_perm.shape
+    dev = x_perm.device
+    dt = _dt(x_perm)
+    if weight_layout is None:
+        weight_layout = LAYOUT_PACKED if dt == MOE_BF16 else LAYOUT_PLAIN
+    if max_slots is None:
+        max_slots = slot_expert.shape[0]
+    y = out if out is not None else torch.empty_like(x_perm)
+    ws = ws if ws is not None else _ws(lib().moe_expert_ffn_workspace_bytes(max_rows, max_slots, d, F, dt), dev)
+    _check(lib().moe_expert_ffn(_ptr(x_perm), _ptr(w1), _ptr(w2), weight_layout, _ptr(slot_offset),
+                                _ptr(slot_expert), _ptr(n_slots), max_rows, max_slots, E, d, F, dt, schedule,
+                                _ptr(y), _ptr(ws), ws.numel(), _stream()))
+    return y
+
+
+def moe_combine(y_perm, x, inv, expert_prob, residual=0, out=None):
+    T, d = x.shape
+    o = out if out is not None else torch.empty_like(x)
+    _check(lib().moe_combine(_ptr(y_perm), _ptr(x), _ptr(inv), _ptr(expert_prob), T, d, _dt(x), int(residual),
+                             _ptr(o), _stream()))
+    return o
+
+
+# --------------------------------------------------------------------------- whole layer
+class MoeLayer:
+    """Preallocated buffers + the chain route -> plan -> dispatch -> expert FFN -> combine for
+    one layer shape.  Pure sequencing of the calls above on the current stream."""
+
+    def __init__(self, T, d, F, E, budget, slot_capacity, dtype, device="cuda", policy=0):
+        self.T, self.d, self.F, self.E, self.R, self.C = T, d, F, E, budget, slot_capacity
+        self.policy = policy
+        self.max_slots = E + budget
+        dev = torch.device(device)
+        dt = MOE_BF16 if dtype == torch.bfloat16 else MOE_F32
+        L = lib()
+        self.route_out = (_i32(T, dev), torch.empty(T, dtype=torch.float32, device=dev))
+        self.route_ws = _ws(L.moe_route_workspace_bytes(T, d, E, dt), dev)
+        self.plan_out = dict(plan_counts=_i32(E, dev), replicas=_i32(E, dev), slot_base=_i32(E + 1, dev),
+                             slot_expert=_i32(E + budget, dev), n_slots=_i32(1, dev))
+        self.disp_out = dict(counts=_i32(E, dev), kept=_i32(E, dev), expert_offset=_i32(E + 1, dev),
+                             slot_offset=_i32(self.max_slots + 1, dev), perm=_i32(T, dev), inv=_i32(T, dev),
+                             x_perm=torch.zeros(T, d, dtype=dtype, device=dev))
+        self.disp_ws = _ws(L.moe_dispatch_workspace_bytes(T, E), dev)
+        self.y_perm = torch.zeros(T, d, dtype=dtype, device=dev)
+        self.ffn_ws = _ws(L.moe_expert_ffn_workspace_bytes(T, self.max_slots, d, F, dt), dev)
+        self.out = torch.empty(T, d, dtype=dtype, device=dev)
+
+    def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
+                out=None, budget=None):
+        idx, prob, _ = moe_route(x, w_router, b_router, out=self.route_out, ws=self.route_ws)
+        R = self.R if budget is None else budget
+        if R != self.R:
+            raise ValueError("budget is fixed by the preallocated slot tables")
+        pl = replica_plan(idx if plan_ids is None else plan_ids, self.E, R, self.C, self.policy, out=self.plan_out)
+        dp = moe_dispatch(x, idx, pl["replicas"], self.E, self.C, self.max_slots, out=self.disp_out,
+                          ws=self.disp_ws)
+        y = moe_expert_ffn(dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"], pl["n_slots"], self.E,
+                           self.F, max_slots=self.max_slots, schedule=schedule, out=self.y_perm, ws=self.ffn_ws)
+        return moe_combine(y, x, dp["inv"], prob, residual, out=self.out if out is None else out)

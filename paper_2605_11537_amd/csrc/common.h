@@ -1,0 +1,97 @@
+// Internal helpers shared by the kernels of the library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/moe_mpmc.h"
+
+namespace moe {
+
+void set_error(const char *fmt, ...);
+
+#define MOE_REQUIRE(cond, code, ...)     \
+    do {                                 \
+        if (!(cond)) {                   \
+            moe::set_error(__VA_ARGS__); \
+            return (code);               \
+        }                                \
+    } while (0)
+
+// Check the launch that was just enqueued.
+#define MOE_CHECK_LAUNCH(what)                                                      \
+    do {                                                                            \
+        hipError_t e__ = hipGetLastError();                                         \
+        if (e__ != hipSuccess) {                                                    \
+            moe::set_error("%s: launch failed: %s", (what), hipGetErrorString(e__)); \
+            return MOE_ERR_HIP;                                                     \
+        }                                                                           \
+    } while (0)
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+constexpr int WAVE = 64;
+
+// ---------------------------------------------------------------- bf16 <-> f32 on device
+typedef unsigned short bf16_t;  // raw bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round to nearest, ties to even; NaN kept quiet
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// XCD-aware remap of a linear workgroup id: hardware deals consecutive workgroup ids to the 8
+// XCDs in turn, so ids that are congruent mod 8 share an L2.  The remap gives each XCD a
+// contiguous range of logical ids, so that neighbours in the logical order (which share
+// operands) meet in one L2.  Needs gridDim.x to be a multiple of 8 to be a bijection; the
+// caller pads the grid and idle ids exit.
+__device__ __forceinline__ int xcd_remap(int bid, int grid)
+{
+    int per = grid >> 3;
+    return (bid & 7) * per + (bid >> 3);
+}
+
+// Exclusive scan of one int per thread over a 1024-thread workgroup.  Returns the prefix and
+// leaves the grand total in *total_out (LDS).  wave_sums is LDS scratch of 16 ints.
+__device__ __forceinline__ int block_scan_excl_1024(int v, int *wave_sums, int *total_out)
+{
+    int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int n = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += n;
+    }
+    if (lane == 63) wave_sums[w] = inc;
+    __syncthreads();
+    if (w == 0) {
+        int s = lane < 16 ? wave_sums[lane] : 0;
+        int si = s;
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+            int n = __shfl_up(si, o, 64);
+            if (lane >= o) si += n;
+        }
+        if (lane < 16) wave_sums[lane] = si - s;
+        if (lane == 15) *total_out = si;
+    }
+    __syncthreads();
+    int r = wave_sums[w] + inc - v;
+    __syncthreads();
+    return r;
+}
+
+}  // namespace moe

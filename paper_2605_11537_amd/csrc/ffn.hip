@@ -1,0 +1,295 @@
+// moe_expert_ffn: grouped expert FFN over experts and their replica slots, and
+// moe_pack_weights: one-time re-layout of static expert weights for the matrix-core kernels.
+//
+//   worklist  one workgroup turns the device-side slot tables into a list of row tiles
+//             (expert, first row, end row); a slot of more than 64 rows gives several tiles,
+//             so the replicas of a hot expert and the tiles inside a replica all run side by
+//             side.  In the "experts" schedule there is one item per logical expert instead
+//             and the kernel walks its rows 64 at a time.
+//   gemm1     h = relu(x_perm * W1[e])   per (row tile, 128-column tile)
+//   gemm2     y_perm = h * W2[e]
+// Grids are sized for the worst case on the host (rows and slots are only known on the
+// device); workgroups beyond the list exit at once.  Workgroup ids are remapped so that the
+// column tiles of one row tile, which share the token rows, run on one XCD.
+#include "gemm_bf16.h"
+
+namespace moe {
+
+constexpr int FFN_BM = 64;    // rows per tile
+constexpr int FFN_BN = 128;   // columns per workgroup (bf16 path)
+
+struct __attribute__((aligned(16))) WorkItem {
+    int expert, row_begin, row_end, pad;
+};
+
+// ------------------------------------------------------------------ weight packing
+// out[((e*(K/8) + k/8)*N + n)*8 + k%8] = in[e][k][n]
+__global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restrict__ in, int K, int N,
+                                                           uint4 *__restrict__ out)
+{
+    const int e = blockIdx.z, kg = blockIdx.y;
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const bf16_t *src = in + ((size_t)e * K + (size_t)kg * 8) * N + n;
+    uint32_t v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        v[j] = (uint32_t)src[(size_t)(2 * j) * N] | ((uint32_t)src[(size_t)(2 * j + 1) * N] << 16);
+    out[((size_t)e * (K / 8) + kg) * N + n] = make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// ------------------------------------------------------------------ work list
+__global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__restrict__ slot_offset,
+                                                            const int32_t *__restrict__ slot_expert,
+                                                            const int32_t *__restrict__ n_slots_p, int max_slots,
+                                                            int max_items, int schedule, WorkItem *__restrict__ items,
+                                                            int32_t *__restrict__ n_items)
+{
+    __shared__ int wave_sums[16];
+    __shared__ int total;
+    int P = n_slots_p[0];
+    if (P > max_slots) P = max_slots;
+    int base = 0;
+    for (int p0 = 0; p0 < P; p0 += 1024) {
+        int p = p0 + threadIdx.x;
+        int cnt = 0, e = -1, r0 = 0, r1 = 0;
+        if (p < P) {
+            e = slot_expert[p];
+            r0 = slot_offset[p];
+            if (schedule == MOE_SCHEDULE_SLOTS) {
+                r1 = slot_offset[p + 1];
+                cnt = (r1 - r0 + FFN_BM - 1) / FFN_BM;
+            } else if (p == 0 || slot_expert[p - 1] != e) {
+                int q = p + 1;
+                while (q < P && slot_expert[q] == e) ++q;
+                r1 = slot_offset[q];
+                cnt = r1 > r0 ? 1 : 0;
+            }
+            if (e < 0) cnt = 0;
+        }
+        int off = base + block_scan_excl_1024(cnt, wave_sums, &total);
+        for (int i = 0; i < cnt; ++i) {
+            if (off + i < max_items) {
+                WorkItem it;
+                it.expert = e;
+                it.pad = 0;
+                if (schedule == MOE_SCHEDULE_SLOTS) {
+                    it.row_begin = r0 + i * FFN_BM;
+                    it.row_end = it.row_begin + FFN_BM < r1 ? it.row_begin + FFN_BM : r1;
+                } else {
+                    it.row_begin = r0;
+                    it.row_end = r1;
+                }
+                items[off + i] = it;
+            }
+        }
+        base += total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) n_items[0] = base < max_items ? base : max_items;
+}
+
+// ------------------------------------------------------------------ bf16 grouped GEMM
+template <bool RELU>
+__global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
+    const bf16_t *__restrict__ A, const bf16_t *__restrict__ Wp, int K, int N, int E,
+    const WorkItem *__restrict__ items, const int32_t *__restrict__ n_items, int max_rows, bf16_t *__restrict__ C)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2>()];
+    const int n_nt = N / FFN_BN;
+    const int lid = xcd_remap(blockIdx.x, gridDim.x);
+    const int item = lid / n_nt, nt = lid - item * n_nt;
+    if (item >= n_items[0]) return;
+    const WorkItem it = items[item];
+    if (it.expert < 0 || it.expert >= E || it.row_begin < 0) return;  // never index weights with a bad id
+    const bf16_t *Bp = Wp + (size_t)it.expert * K * N;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int row_end = it.row_end < max_rows ? it.row_end : max_rows;
+    for (int r0 = it.row_begin; r0 < row_end; r0 += FFN_BM) {
+        const int nrows = row_end - r0 < FFN_BM ? row_end - r0 : FFN_BM;
+        f32x16_t acc[2][1];
+        zero_acc<2, 1>(acc);
+        gemm_tile_bf16<2, 1>(A + (size_t)r0 * K, K, nrows, Bp, N, nt * FFN_BN, K, lds, acc);
+        const int col = nt * FFN_BN + w * 32 + (lane & 31);
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                int r = mb * 32 + acc_row(v, lane);
+                if (r < nrows) {
+                    float val = acc[mb][0][v];
+                    if (RELU) val = val > 0.f ? val : 0.f;
+                    C[(size_t)(r0 + r) * N + col] = f32_to_bf16(val);
+                }
+            }
+    }
+}
+
+// ------------------------------------------------------------------ fp32 grouped GEMM (plain weights)
+// 64x64 tile, 256 threads, 4x4 outputs per thread, k ascending.
+template <bool RELU>
+__global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W,
+                                                           int K, int N, int E, const WorkItem *__restrict__ items,
+                                                           const int32_t *__restrict__ n_items, int max_rows,
+                                                           float *__restrict__ C)
+{
+    __shared__ float As[16][64 + 4];
+    __shared__ float Bs[16][64];
+    const int n_nt = N / 64;
+    const int item = blockIdx.x / n_nt, nt = blockIdx.x - item * n_nt;
+    if (item >= n_items[0]) return;
+    const WorkItem it = items[item];
+    if (it.expert < 0 || it.expert >= E || it.row_begin < 0) return;
+    const float *B = W + (size_t)it.expert * K * N + nt * 64;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int row_end = it.row_end < max_rows ? it.row_end : max_rows;
+    for (int r0 = it.row_begin; r0 < row_end; r0 += FFN_BM) {
+        const int nrows = row_end - r0 < FFN_BM ? row_end - r0 : FFN_BM;
+        float acc[4][4] = {};
+        for (int k0 = 0; k0 < K; k0 += 16) {
+            {   // A chunk 64 rows x 16 k: thread loads 4 consecutive k of one row
+                int r = threadIdx.x >> 2, kq = (threadIdx.x & 3) * 4;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (r < nrows) v = *reinterpret_cast<const float4 *>(A + (size_t)(r0 + r) * K + k0 + kq);
+                As[kq + 0][r] = v.x;
+                As[kq + 1][r] = v.y;
+                As[kq + 2][r] = v.z;
+                As[kq + 3][r] = v.w;
+                int kb = threadIdx.x >> 4, nb = (threadIdx.x & 15) * 4;
+                *reinterpret_cast<float4 *>(&Bs[kb][nb]) =
+                    *reinterpret_cast<const float4 *>(B + (size_t)(k0 + kb) * N + nb);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                float a[4], b[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) b[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int r = ty * 4 + i;
+            if (r < nrows) {
+                float4 o;
+                o.x = RELU ? fmaxf(acc[i][0], 0.f) : acc[i][0];
+                o.y = RELU ? fmaxf(acc[i][1], 0.f) : acc[i][1];
+                o.z = RELU ? fmaxf(acc[i][2], 0.f) : acc[i][2];
+                o.w = RELU ? fmaxf(acc[i][3], 0.f) : acc[i][3];
+                *reinterpret_cast<float4 *>(C + (size_t)(r0 + r) * N + nt * 64 + tx * 4) = o;
+            }
+        }
+    }
+}
+
+static inline int ffn_max_items(int max_rows, int max_slots) { return max_slots + max_rows / FFN_BM + 1; }
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" size_t moe_packed_weights_bytes(int E, int K, int N, int dtype)
+{
+    if (E <= 0 || K <= 0 || N <= 0 || dtype != MOE_BF16) return 0;
+    return (size_t)E * K * N * 2;
+}
+
+extern "C" int moe_pack_weights(const void *w, int E, int K, int N, int dtype, void *w_packed, void *stream)
+{
+    MOE_REQUIRE(E > 0 && K > 0 && N > 0, MOE_ERR_INVALID_ARG, "moe_pack_weights: E=%d K=%d N=%d out of range", E, K, N);
+    MOE_REQUIRE(dtype == MOE_BF16, MOE_ERR_UNSUPPORTED, "moe_pack_weights: only MOE_BF16 weights are packed");
+    MOE_REQUIRE(K % 8 == 0, MOE_ERR_INVALID_ARG, "moe_pack_weights: K=%d is not a multiple of 8", K);
+    MOE_REQUIRE(E <= 65535 && K / 8 <= 65535, MOE_ERR_UNSUPPORTED, "moe_pack_weights: E or K too large");
+    MOE_REQUIRE(w && w_packed && w != w_packed, MOE_ERR_INVALID_ARG, "moe_pack_weights: null or aliased pointer");
+    MOE_REQUIRE(aligned16(w_packed), MOE_ERR_INVALID_ARG, "moe_pack_weights: output misaligned");
+    hipLaunchKernelGGL(pack_weights_kernel, dim3(ceil_div(N, 256), K / 8, E), dim3(256), 0, (hipStream_t)stream,
+                       (const bf16_t *)w, K, N, (uint4 *)w_packed);
+    MOE_CHECK_LAUNCH("moe_pack_weights");
+    return MOE_OK;
+}
+
+extern "C" size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, int d, int F, int dtype)
+{
+    if (max_rows < 0 || max_slots <= 0 || d <= 0 || F <= 0) return 0;
+    size_t esz = dtype == MOE_F32 ? 4 : 2;
+    size_t h = align_up((size_t)(max_rows > 0 ? max_rows : 1) * F * esz, 256);
+    size_t items = align_up((size_t)ffn_max_items(max_rows, max_slots) * sizeof(WorkItem), 256);
+    return h + items + 256;
+}
+
+extern "C" int moe_expert_ffn(const void *x_perm, const void *w1, const void *w2, int weight_layout,
+                              const int32_t *slot_offset, const int32_t *slot_expert, const int32_t *n_slots,
+                              int max_rows, int max_slots, int E, int d, int F, int dtype, int schedule,
+                              void *y_perm, void *ws, size_t ws_bytes, void *stream)
+{
+    MOE_REQUIRE(max_rows >= 0 && max_slots > 0 && E > 0 && d > 0 && F > 0, MOE_ERR_INVALID_ARG,
+                "moe_expert_ffn: max_rows=%d max_slots=%d E=%d d=%d F=%d out of range", max_rows, max_slots, E, d,
+                F);
+    MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_INVALID_ARG, "moe_expert_ffn: unknown dtype %d", dtype);
+    MOE_REQUIRE(schedule == MOE_SCHEDULE_SLOTS || schedule == MOE_SCHEDULE_EXPERTS, MOE_ERR_INVALID_ARG,
+                "moe_expert_ffn: unknown schedule %d", schedule);
+    MOE_REQUIRE(weight_layout == MOE_LAYOUT_PLAIN || weight_layout == MOE_LAYOUT_PACKED, MOE_ERR_INVALID_ARG,
+                "moe_expert_ffn: unknown weight layout %d", weight_layout);
+    MOE_REQUIRE(max_slots <= MOE_MAX_SLOTS, MOE_ERR_UNSUPPORTED, "moe_expert_ffn: max_slots=%d exceeds %d",
+                max_slots, MOE_MAX_SLOTS);
+    if (dtype == MOE_BF16) {
+        MOE_REQUIRE(weight_layout == MOE_LAYOUT_PACKED, MOE_ERR_UNSUPPORTED,
+                    "moe_expert_ffn: bf16 weights must be packed with moe_pack_weights");
+        MOE_REQUIRE(d % FFN_BN == 0 && F % FFN_BN == 0, MOE_ERR_UNSUPPORTED,
+                    "moe_expert_ffn: bf16 path needs d and F multiples of %d (d=%d F=%d)", FFN_BN, d, F);
+    } else {
+        MOE_REQUIRE(weight_layout == MOE_LAYOUT_PLAIN, MOE_ERR_UNSUPPORTED,
+                    "moe_expert_ffn: fp32 weights are taken in the plain layout");
+        MOE_REQUIRE(d % 64 == 0 && F % 64 == 0, MOE_ERR_UNSUPPORTED,
+                    "moe_expert_ffn: fp32 path needs d and F multiples of 64 (d=%d F=%d)", d, F);
+    }
+    MOE_REQUIRE(x_perm && w1 && w2 && slot_offset && slot_expert && n_slots && y_perm, MOE_ERR_INVALID_ARG,
+                "moe_expert_ffn: null pointer");
+    MOE_REQUIRE(aligned16(x_perm) && aligned16(w1) && aligned16(w2) && aligned16(y_perm), MOE_ERR_INVALID_ARG,
+                "moe_expert_ffn: tensor misaligned");
+    size_t need = moe_expert_ffn_workspace_bytes(max_rows, max_slots, d, F, dtype);
+    MOE_REQUIRE(ws && aligned16(ws) && ws_bytes >= need, MOE_ERR_WORKSPACE,
+                "moe_expert_ffn: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+    if (max_rows == 0) return MOE_OK;
+
+    hipStream_t st = (hipStream_t)stream;
+    size_t esz = dtype == MOE_F32 ? 4 : 2;
+    char *p = (char *)ws;
+    void *h = p;
+    p += align_up((size_t)max_rows * F * esz, 256);
+    WorkItem *items = (WorkItem *)p;
+    int max_items = ffn_max_items(max_rows, max_slots);
+    p += align_up((size_t)max_items * sizeof(WorkItem), 256);
+    int32_t *n_items = (int32_t *)p;
+
+    hipLaunchKernelGGL(ffn_worklist_kernel, dim3(1), dim3(1024), 0, st, slot_offset, slot_expert, n_slots, max_slots,
+                       max_items, schedule, items, n_items);
+    MOE_CHECK_LAUNCH("moe_expert_ffn/worklist");
+    int grid_items = schedule == MOE_SCHEDULE_SLOTS ? max_items : (max_slots < max_items ? max_slots : max_items);
+    if (dtype == MOE_BF16) {
+        int g1 = (int)align_up((size_t)grid_items * (F / FFN_BN), 8);
+        int g2 = (int)align_up((size_t)grid_items * (d / FFN_BN), 8);
+        hipLaunchKernelGGL(ffn_gemm_bf16_kernel<true>, dim3(g1), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x_perm,
+                           (const bf16_t *)w1, d, F, E, items, n_items, max_rows, (bf16_t *)h);
+        MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
+        hipLaunchKernelGGL(ffn_gemm_bf16_kernel<false>, dim3(g2), dim3(GEMM_THREADS), 0, st, (const bf16_t *)h,
+                           (const bf16_t *)w2, F, d, E, items, n_items, max_rows, (bf16_t *)y_perm);
+        MOE_CHECK_LAUNCH("moe_expert_ffn/gemm2");
+    } else {
+        int g1 = grid_items * (F / 64), g2 = grid_items * (d / 64);
+        hipLaunchKernelGGL(ffn_gemm_f32_kernel<true>, dim3(g1), dim3(256), 0, st, (const float *)x_perm,
+                           (const float *)w1, d, F, E, items, n_items, max_rows, (float *)h);
+        MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
+        hipLaunchKernelGGL(ffn_gemm_f32_kernel<false>, dim3(g2), dim3(256), 0, st, (const float *)h,
+                           (const float *)w2, F, d, E, items, n_items, max_rows, (float *)y_perm);
+        MOE_CHECK_LAUNCH("moe_expert_ffn/gemm2");
+    }
+    return MOE_OK;
+}

@@ -1,0 +1,205 @@
+// replica_plan: per-expert replica counts from (predicted) expert ids, within a slot budget.
+//
+// One workgroup of 1024 threads.  All threads build the histogram of ids in LDS (ids that
+// share a wavefront load are pre-counted with ballots, so a hot expert does not serialise the
+// LDS atomics).  Wavefront 0 then runs the integer allocation entirely in registers: lane l
+// owns experts l, l+64, ..., sums and arg-max searches are wavefront reductions, so the
+// one-by-one hand-out of the slots left by the floors needs no barrier.  All threads finally
+// scan the replica counts into slot_base and write the slot -> expert table.
+#include "common.h"
+
+namespace moe {
+
+constexpr int PLAN_THREADS = 1024;
+constexpr int PLAN_PER_LANE = MOE_MAX_EXPERTS / WAVE;  // experts per lane of wavefront 0
+
+__device__ __forceinline__ long long wave_sum_ll(long long v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__global__ __launch_bounds__(PLAN_THREADS) void replica_plan_kernel(
+    const int32_t *__restrict__ idx, int T, int E, int nbits, int R, int C, int policy,
+    int32_t *__restrict__ plan_counts, int32_t *__restrict__ replicas, int32_t *__restrict__ slot_base,
+    int32_t *__restrict__ slot_expert, int32_t *__restrict__ n_slots)
+{
+    __shared__ int hist[MOE_MAX_EXPERTS];
+    __shared__ int rep[MOE_MAX_EXPERTS];
+    __shared__ int wave_sums[16];
+    __shared__ int total_p;
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int e = tid; e < MOE_MAX_EXPERTS; e += PLAN_THREADS) {
+        hist[e] = 0;
+        rep[e] = 0;
+    }
+    __syncthreads();
+    for (int t0 = 0; t0 < T; t0 += PLAN_THREADS) {
+        int t = t0 + tid;
+        int e = t < T ? idx[t] : -1;
+        bool valid = e >= 0 && e < E;
+        unsigned long long mask = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            bool bit = (e >> b) & 1;
+            unsigned long long bal = __ballot(bit);
+            mask &= bit ? bal : ~bal;
+        }
+        if (valid && (mask & ((1ull << lane) - 1ull)) == 0) atomicAdd(&hist[e], __popcll(mask));
+    }
+    __syncthreads();
+
+    if (tid < WAVE) {
+        int n[PLAN_PER_LANE], r[PLAN_PER_LANE];
+        long long want[PLAN_PER_LANE];
+        long long dsum = 0;
+#pragma unroll
+        for (int i = 0; i < PLAN_PER_LANE; ++i) {
+            int e = lane + i * WAVE;
+            n[i] = e < E ? hist[e] : 0;
+            long long w = ((long long)n[i] + C - 1) / C - 1;
+            want[i] = (e < E && w > 0) ? w : 0;
+            r[i] = 1;
+            dsum += want[i];
+        }
+        const long long D = wave_sum_ll(dsum);
+        if (D <= (long long)R) {
+#pragma unroll
+            for (int i = 0; i < PLAN_PER_LANE; ++i) r[i] += (int)want[i];
+        } else {
+            long long left = R;
+            if (policy == 0) {
+                long long used = 0;
+#pragma unroll
+                for (int i = 0; i < PLAN_PER_LANE; ++i) {
+                    long long extra = (long long)R * want[i] / D;
+                    r[i] += (int)extra;
+                    used += extra;
+                }
+                left -= wave_sum_ll(used);
+            } else {
+                for (;;) {
+                    long long nw = 0;
+#pragma unroll
+                    for (int i = 0; i < PLAN_PER_LANE; ++i) nw += (long long)r[i] - 1 < want[i];
+                    nw = wave_sum_ll(nw);
+                    if (nw == 0) break;
+                    long long q = left / nw;
+                    if (q == 0) break;
+                    long long given = 0;
+#pragma unroll
+                    for (int i = 0; i < PLAN_PER_LANE; ++i) {
+                        long long unmet = want[i] - ((long long)r[i] - 1);
+                        if (unmet > 0) {
+                            long long g = q < unmet ? q : unmet;
+                            r[i] += (int)g;
+                            given += g;
+                        }
+                    }
+                    left -= wave_sum_ll(given);
+                }
+            }
+            // the slots still left go one at a time to the most loaded expert per slot
+            while (left > 0) {
+                int bn = 0, br = 1, be = -1;
+#pragma unroll
+                for (int i = 0; i < PLAN_PER_LANE; ++i) {
+                    bool open = (long long)r[i] - 1 < want[i];
+                    // ascending expert id within the lane: strict '>' keeps the lowest id
+                    if (open && (be < 0 || (long long)n[i] * br > (long long)bn * r[i])) {
+                        bn = n[i];
+                        br = r[i];
+                        be = lane + i * WAVE;
+                    }
+                }
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) {
+                    int on = __shfl_xor(bn, o, 64), orr = __shfl_xor(br, o, 64), oe = __shfl_xor(be, o, 64);
+                    if (oe >= 0) {
+                        long long lhs = (long long)on * br, rhs = (long long)bn * orr;
+                        if (be < 0 || lhs > rhs || (lhs == rhs && oe < be)) {
+                            bn = on;
+                            br = orr;
+                            be = oe;
+                        }
+                    }
+                }
+                if (be < 0) break;
+#pragma unroll
+                for (int i = 0; i < PLAN_PER_LANE; ++i)
+                    if (be == lane + i * WAVE) r[i] += 1;
+                left -= 1;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PLAN_PER_LANE; ++i) {
+            int e = lane + i * WAVE;
+            if (e < E) {
+                rep[e] = r[i];
+                replicas[e] = r[i];
+                plan_counts[e] = n[i];
+            }
+        }
+    }
+    __syncthreads();
+
+    // slot_base = exclusive scan of the replica counts (one expert per thread)
+    int v = tid < E ? rep[tid] : 0;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int nn = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += nn;
+    }
+    if (lane == 63) wave_sums[tid >> 6] = inc;
+    __syncthreads();
+    if (tid < WAVE) {
+        int s = lane < 16 ? wave_sums[lane] : 0, si = s;
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) {
+            int nn = __shfl_up(si, o, 64);
+            if (lane >= o) si += nn;
+        }
+        if (lane < 16) wave_sums[lane] = si - s;
+        if (lane == 15) total_p = si;
+    }
+    __syncthreads();
+    int base = wave_sums[tid >> 6] + inc - v;
+    int P = total_p;
+    if (tid < E) {
+        if (slot_base) slot_base[tid] = base;
+        if (slot_expert)
+            for (int k = 0; k < v; ++k) slot_expert[base + k] = tid;
+    }
+    if (tid == 0) {
+        if (slot_base) slot_base[E] = P;
+        if (n_slots) n_slots[0] = P;
+    }
+    if (slot_expert)
+        for (int p = P + tid; p < E + R; p += PLAN_THREADS) slot_expert[p] = -1;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" int replica_plan(const int32_t *idx, int T, int E, int budget, int slot_capacity, int policy,
+                            int32_t *plan_counts, int32_t *replicas, int32_t *slot_base,
+                            int32_t *slot_expert, int32_t *n_slots, void *stream)
+{
+    MOE_REQUIRE(T >= 0 && E > 0 && budget >= 0 && slot_capacity >= 1, MOE_ERR_INVALID_ARG,
+                "replica_plan: T=%d E=%d budget=%d slot_capacity=%d out of range", T, E, budget,
+                slot_capacity);
+    MOE_REQUIRE(policy == 0 || policy == 1, MOE_ERR_INVALID_ARG, "replica_plan: unknown policy %d", policy);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "replica_plan: E=%d exceeds %d", E, MOE_MAX_EXPERTS);
+    MOE_REQUIRE((long long)E + budget <= MOE_MAX_SLOTS, MOE_ERR_UNSUPPORTED,
+                "replica_plan: E+budget=%lld exceeds %d", (long long)E + budget, MOE_MAX_SLOTS);
+    MOE_REQUIRE((T == 0 || idx) && plan_counts && replicas, MOE_ERR_INVALID_ARG, "replica_plan: null pointer");
+    int nbits = 0;
+    while ((1 << nbits) < E) ++nbits;
+    hipLaunchKernelGGL(replica_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, (hipStream_t)stream, idx, T, E,
+                       nbits, budget, slot_capacity, policy, plan_counts, replicas, slot_base, slot_expert,
+                       n_slots);
+    MOE_CHECK_LAUNCH("replica_plan");
+    return MOE_OK;
+}

@@ -1,0 +1,12 @@
+// Host-side entry points of route.hip that sru_predict reuses (its head is a router-shaped
+// product + argmax, its projections need the same packed weight image).
+#pragma once
+#include "common.h"
+
+namespace moe {
+size_t route_ws_bytes(int d, int E, int dtype);
+int route_launch(const void *x, const void *w_router, const float *b_router, int T, int d, int E, int dtype,
+                 int32_t *idx, float *prob, float *logits_opt, void *ws, hipStream_t st, const char *who);
+// in [K][N] bf16 row-major -> packed image, element ((k/8)*N + n)*8 + k%8
+int pack_matrix_launch(const void *in, int K, int N, void *out, hipStream_t st, const char *who);
+}  // namespace moe

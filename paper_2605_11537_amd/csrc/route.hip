@@ -1,0 +1,224 @@
+// moe_route: router logits, softmax probability of the winner and argmax, fused: the logits
+// of a 64-token tile live in accumulators / LDS and reach HBM only when the caller asks.
+//
+//   bf16, E a multiple of 128 (<= 256): matrix-core kernel.  The [d,E] router matrix is first
+//     re-laid into the packed k-major image the MFMA B operand wants (a few hundred KB, one
+//     small kernel into the workspace), then each workgroup multiplies a 64-token tile with
+//     all E columns and reduces each row (max, first arg-max, sum of exponentials) in LDS.
+//   anything else (fp32 tensors, small or odd E): one wavefront per token, lanes over
+//     experts, binary32 FMA in ascending k.
+#include "gemm_bf16.h"
+#include "route.h"
+
+namespace moe {
+
+constexpr int RT_BM = 64;
+
+__device__ __forceinline__ void argmax_merge(float &v, int &i, float ov, int oi)
+{
+    if (ov > v || (ov == v && oi < i)) {
+        v = ov;
+        i = oi;
+    }
+}
+
+// in [K][N] bf16 row-major -> packed image ((k/8)*N + n)*8 + k%8
+__global__ __launch_bounds__(256) void pack_matrix_kernel(const bf16_t *__restrict__ in, int K, int N,
+                                                          uint4 *__restrict__ out)
+{
+    int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= (K / 8) * N) return;
+    int kg = i / N, n = i - kg * N;
+    const bf16_t *src = in + (size_t)kg * 8 * N + n;
+    uint32_t v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        v[j] = (uint32_t)src[(size_t)(2 * j) * N] | ((uint32_t)src[(size_t)(2 * j + 1) * N] << 16);
+    out[i] = make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+template <int NB>
+__global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *__restrict__ x,
+                                                                  const bf16_t *__restrict__ wr_packed,
+                                                                  const float *__restrict__ bias, int T, int d,
+                                                                  int32_t *__restrict__ idx, float *__restrict__ prob,
+                                                                  float *__restrict__ logits_opt)
+{
+    constexpr int E = NB * 128;
+    constexpr int LDL = E + 4;
+    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2>()];
+    __shared__ float tile[32 * LDL];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int row0 = blockIdx.x * RT_BM;
+    const int nrows = T - row0 < RT_BM ? T - row0 : RT_BM;
+    f32x16_t acc[2][NB];
+    zero_acc<2, NB>(acc);
+    gemm_tile_bf16<2, NB>(x + (size_t)row0 * d, d, nrows, wr_packed, E, 0, d, lds, acc);
+
+    float b[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) b[nb] = bias ? bias[(w * NB + nb) * 32 + (lane & 31)] : 0.f;
+
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                tile[acc_row(v, lane) * LDL + (w * NB + nb) * 32 + (lane & 31)] = acc[mb][nb][v] + b[nb];
+        __syncthreads();
+        // 8 threads per row, each over E/8 strided columns, then a 3-step butterfly
+        const int r = tid >> 3, sub = tid & 7;
+        const float *row = tile + r * LDL;
+        float best = row[sub];
+        int bi = sub;
+        for (int c = sub + 8; c < E; c += 8) argmax_merge(best, bi, row[c], c);
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) {
+            float ov = __shfl_xor(best, o, 64);
+            int oi = __shfl_xor(bi, o, 64);
+            argmax_merge(best, bi, ov, oi);
+        }
+        float z = 0.f;
+        for (int c = sub; c < E; c += 8) z += expf(row[c] - best);
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) z += __shfl_xor(z, o, 64);
+        const int grow = row0 + mb * 32 + r;
+        if (sub == 0 && mb * 32 + r < nrows) {
+            idx[grow] = bi;
+            prob[grow] = 1.f / z;
+        }
+        if (logits_opt) {
+            for (int i = tid; i < 32 * E; i += GEMM_THREADS) {
+                int rr = i / E, cc = i - rr * E;
+                if (mb * 32 + rr < nrows) logits_opt[(size_t)(row0 + mb * 32 + rr) * E + cc] = tile[rr * LDL + cc];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// one wavefront per token; lanes over experts
+template <bool BF16>
+__global__ __launch_bounds__(256) void route_generic_kernel(const void *__restrict__ xv, const void *__restrict__ wv,
+                                                            const float *__restrict__ bias, int T, int d, int E,
+                                                            int32_t *__restrict__ idx, float *__restrict__ prob,
+                                                            float *__restrict__ logits_opt)
+{
+    const int lane = threadIdx.x & 63;
+    const int s = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (s >= T) return;
+    constexpr int PER = MOE_MAX_EXPERTS / WAVE;
+    float l[PER];
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        int e = lane + i * WAVE;
+        l[i] = -INFINITY;
+        if (e < E) {
+            float acc = 0.f;
+            if (BF16) {
+                const bf16_t *x = (const bf16_t *)xv + (size_t)s * d;
+                const bf16_t *w = (const bf16_t *)wv + e;
+                for (int k = 0; k < d; ++k) acc = fmaf(bf16_to_f32(x[k]), bf16_to_f32(w[(size_t)k * E]), acc);
+            } else {
+                const float *x = (const float *)xv + (size_t)s * d;
+                const float *w = (const float *)wv + e;
+                for (int k = 0; k < d; ++k) acc = fmaf(x[k], w[(size_t)k * E], acc);
+            }
+            l[i] = acc + (bias ? bias[e] : 0.f);
+            if (logits_opt) logits_opt[(size_t)s * E + e] = l[i];
+            argmax_merge(best, bi, l[i], e);
+        }
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        float ov = __shfl_xor(best, o, 64);
+        int oi = __shfl_xor(bi, o, 64);
+        argmax_merge(best, bi, ov, oi);
+    }
+    float z = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+        if (lane + i * WAVE < E) z += expf(l[i] - best);
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) z += __shfl_xor(z, o, 64);
+    if (lane == 0) {
+        idx[s] = bi;
+        prob[s] = 1.f / z;
+    }
+}
+
+static inline bool route_uses_mfma(int d, int E, int dtype)
+{
+    return dtype == MOE_BF16 && (E == 128 || E == 256) && d % GEMM_BK == 0;
+}
+
+int pack_matrix_launch(const void *in, int K, int N, void *out, hipStream_t st, const char *who)
+{
+    int n = (K / 8) * N;
+    hipLaunchKernelGGL(pack_matrix_kernel, dim3(ceil_div(n, 256)), dim3(256), 0, st, (const bf16_t *)in, K, N,
+                       (uint4 *)out);
+    MOE_CHECK_LAUNCH(who);
+    return MOE_OK;
+}
+
+// shared with sru_predict (its head is the same product + argmax)
+int route_launch(const void *x, const void *w_router, const float *b_router, int T, int d, int E, int dtype,
+                 int32_t *idx, float *prob, float *logits_opt, void *ws, hipStream_t st, const char *who)
+{
+    if (route_uses_mfma(d, E, dtype)) {
+        int rc = pack_matrix_launch(w_router, d, E, ws, st, who);
+        if (rc != MOE_OK) return rc;
+        int grid = ceil_div(T, RT_BM);
+        if (E == 128)
+            hipLaunchKernelGGL(route_mfma_kernel<1>, dim3(grid), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x,
+                               (const bf16_t *)ws, b_router, T, d, idx, prob, logits_opt);
+        else
+            hipLaunchKernelGGL(route_mfma_kernel<2>, dim3(grid), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x,
+                               (const bf16_t *)ws, b_router, T, d, idx, prob, logits_opt);
+    } else if (dtype == MOE_BF16) {
+        hipLaunchKernelGGL(route_generic_kernel<true>, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, w_router, b_router, T,
+                           d, E, idx, prob, logits_opt);
+    } else {
+        hipLaunchKernelGGL(route_generic_kernel<false>, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, w_router, b_router,
+                           T, d, E, idx, prob, logits_opt);
+    }
+    MOE_CHECK_LAUNCH(who);
+    return MOE_OK;
+}
+
+size_t route_ws_bytes(int d, int E, int dtype)
+{
+    return route_uses_mfma(d, E, dtype) ? align_up((size_t)d * E * 2, 256) : 256;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" size_t moe_route_workspace_bytes(int T, int d, int E, int dtype)
+{
+    (void)T;
+    if (d <= 0 || E <= 0) return 0;
+    return route_ws_bytes(d, E, dtype);
+}
+
+extern "C" int moe_route(const void *x, const void *w_router, const float *b_router, int T, int d, int E, int dtype,
+                         int32_t *expert_idx, float *expert_prob, float *logits_opt, void *ws, size_t ws_bytes,
+                         void *stream)
+{
+    MOE_REQUIRE(T >= 0 && d > 0 && E > 0, MOE_ERR_INVALID_ARG, "moe_route: T=%d d=%d E=%d out of range", T, d, E);
+    MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_INVALID_ARG, "moe_route: unknown dtype %d", dtype);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_route: E=%d exceeds %d", E, MOE_MAX_EXPERTS);
+    MOE_REQUIRE(d % 8 == 0, MOE_ERR_INVALID_ARG, "moe_route: d=%d is not a multiple of 8", d);
+    if (T == 0) return MOE_OK;
+    MOE_REQUIRE(x && w_router && expert_idx && expert_prob, MOE_ERR_INVALID_ARG, "moe_route: null pointer");
+    MOE_REQUIRE(aligned16(x) && aligned16(w_router), MOE_ERR_INVALID_ARG, "moe_route: tensor misaligned");
+    size_t need = route_ws_bytes(d, E, dtype);
+    MOE_REQUIRE(ws && aligned16(ws) && ws_bytes >= need, MOE_ERR_WORKSPACE,
+                "moe_route: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+    return route_launch(x, w_router, b_router, T, d, E, dtype, expert_idx, expert_prob, logits_opt, ws,
+                        (hipStream_t)stream, "moe_route");
+}

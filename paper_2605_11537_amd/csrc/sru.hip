@@ -1,0 +1,182 @@
+// sru_predict: SRU stack + linear head + argmax, the expert predictor.
+//
+// Per layer: (1) the concatenated weight [n_in, k*n_h] is re-laid into the packed image the
+// MFMA B operand wants (small, into the workspace); (2) one matrix-core product
+// U = X * [W | W_f | W_r | (W_h)] for all B*L tokens at once (the part of the SRU that is
+// parallel over time); (3) the recurrence.  The gates depend on the input only, so
+// c_t = f_t c_{t-1} + (1-f_t) x'_t is a linear recurrence in c: a workgroup takes 64 channels
+// of one sequence and cuts the time axis into 16 chunks, one wavefront each; every wavefront
+// first composes its chunk into (A, B) with c_out = A c_in + B, the carries are chained
+// through LDS, and each wavefront then re-runs its chunk from its true carry-in and writes
+// h_t.  The head is a router-shaped product + argmax and reuses that kernel.
+#include "gemm_bf16.h"
+#include "route.h"
+
+namespace moe {
+
+constexpr int SRU_CHUNKS = 16;
+
+// U[T, N] (fp32) = X[T, K] (bf16) * packed W
+__global__ __launch_bounds__(GEMM_THREADS) void sru_proj_kernel(const bf16_t *__restrict__ X,
+                                                                const bf16_t *__restrict__ Wp, int T, int K, int N,
+                                                                float *__restrict__ U)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2>()];
+    const int n_nt = N / 128;
+    const int mt = blockIdx.x / n_nt, nt = blockIdx.x - mt * n_nt;
+    const int row0 = mt * 64;
+    const int nrows = T - row0 < 64 ? T - row0 : 64;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    f32x16_t acc[2][1];
+    zero_acc<2, 1>(acc);
+    gemm_tile_bf16<2, 1>(X + (size_t)row0 * K, K, nrows, Wp, N, nt * 128, K, lds, acc);
+    const int col = nt * 128 + w * 32 + (lane & 31);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            int r = mb * 32 + acc_row(v, lane);
+            if (r < nrows) U[(size_t)(row0 + r) * N + col] = acc[mb][0][v];
+        }
+}
+
+__device__ __forceinline__ float sigmoidf_(float v) { return 1.f / (1.f + expf(-v)); }
+
+// grid (n_h/64, B); block 64 channels x SRU_CHUNKS time chunks
+__global__ __launch_bounds__(64 * SRU_CHUNKS) void sru_scan_kernel(const float *__restrict__ U,
+                                                                   const bf16_t *__restrict__ x_in, int L, int n_h,
+                                                                   int k, const float *__restrict__ b_f,
+                                                                   const float *__restrict__ b_r,
+                                                                   bf16_t *__restrict__ h_out)
+{
+    __shared__ float carry_a[SRU_CHUNKS][64], carry_b[SRU_CHUNKS][64];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + lane;
+    const int b = blockIdx.y;
+    const int ncol = k * n_h;
+    const int cl = (L + SRU_CHUNKS - 1) / SRU_CHUNKS;
+    const int t0 = q * cl, t1 = (t0 + cl < L) ? t0 + cl : L;
+    const float bf = b_f ? b_f[j] : 0.f, br = b_r ? b_r[j] : 0.f;
+    const float *u = U + (size_t)b * L * ncol + j;
+
+    float a = 1.f, c = 0.f;
+#pragma unroll 4
+    for (int t = t0; t < t1; ++t) {
+        const float *ut = u + (size_t)t * ncol;
+        float f = sigmoidf_(ut[n_h] + bf);
+        a *= f;
+        c = f * c + (1.f - f) * ut[0];
+    }
+    carry_a[q][lane] = a;
+    carry_b[q][lane] = c;
+    __syncthreads();
+    c = 0.f;
+    for (int p = 0; p < q; ++p) c = carry_a[p][lane] * c + carry_b[p][lane];
+
+    const bf16_t *xi = x_in + (size_t)b * L * n_h + j;   // only read when k == 3 (n_in == n_h)
+    bf16_t *ho = h_out + (size_t)b * L * n_h + j;
+#pragma unroll 4
+    for (int t = t0; t < t1; ++t) {
+        const float *ut = u + (size_t)t * ncol;
+        float f = sigmoidf_(ut[n_h] + bf);
+        float r = sigmoidf_(ut[2 * n_h] + br);
+        c = f * c + (1.f - f) * ut[0];
+        float hw = k == 4 ? ut[3 * n_h] : bf16_to_f32(xi[(size_t)t * n_h]);
+        ho[(size_t)t * n_h] = f32_to_bf16(r * tanhf(c) + (1.f - r) * hw);
+    }
+}
+
+struct SruWs {
+    size_t u, h0, h1, wp, rws, prob, total;
+};
+
+static SruWs sru_ws_layout(const sru_weights *w, int B, int L)
+{
+    SruWs s;
+    size_t T = (size_t)B * L;
+    if (T == 0) T = 1;
+    int wide = w->n_in > w->n_hidden ? w->n_in : w->n_hidden;
+    size_t off = 0;
+    s.u = off;
+    off += align_up(T * 4 * (size_t)w->n_hidden * sizeof(float), 256);
+    s.h0 = off;
+    off += align_up(T * (size_t)w->n_hidden * 2, 256);
+    s.h1 = off;
+    off += align_up(T * (size_t)w->n_hidden * 2, 256);
+    s.wp = off;
+    off += align_up((size_t)wide * 4 * w->n_hidden * 2, 256);
+    s.rws = off;
+    off += route_ws_bytes(w->n_hidden, w->n_out, MOE_BF16);
+    s.prob = off;
+    off += align_up(T * sizeof(float), 256);
+    s.total = off;
+    return s;
+}
+
+static int sru_check(const sru_weights *w, int B, int L, int dtype)
+{
+    MOE_REQUIRE(w, MOE_ERR_INVALID_ARG, "sru_predict: null weights");
+    MOE_REQUIRE(B >= 0 && L > 0 && w->n_layers > 0 && w->n_in > 0 && w->n_hidden > 0 && w->n_out > 0,
+                MOE_ERR_INVALID_ARG, "sru_predict: B=%d L=%d layers=%d n_in=%d n_hidden=%d n_out=%d out of range", B, L,
+                w->n_layers, w->n_in, w->n_hidden, w->n_out);
+    MOE_REQUIRE((long long)B * L <= 0x7fffffffLL / 4096, MOE_ERR_UNSUPPORTED, "sru_predict: B*L too large");
+    MOE_REQUIRE(dtype == MOE_BF16, MOE_ERR_UNSUPPORTED, "sru_predict: only MOE_BF16 is built");
+    MOE_REQUIRE(w->n_in % 64 == 0 && w->n_hidden % 64 == 0, MOE_ERR_UNSUPPORTED,
+                "sru_predict: n_in=%d and n_hidden=%d must be multiples of 64", w->n_in, w->n_hidden);
+    MOE_REQUIRE(w->n_out <= MOE_MAX_EXPERTS && w->n_out % 8 == 0, MOE_ERR_UNSUPPORTED,
+                "sru_predict: n_out=%d must be a multiple of 8 and at most %d", w->n_out, MOE_MAX_EXPERTS);
+    MOE_REQUIRE(B <= 65535, MOE_ERR_UNSUPPORTED, "sru_predict: B=%d exceeds 65535", B);
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" size_t sru_predict_workspace_bytes(const sru_weights *w, int B, int L, int dtype)
+{
+    if (sru_check(w, B, L, dtype) != MOE_OK) return 0;
+    return sru_ws_layout(w, B, L).total;
+}
+
+extern "C" int sru_predict(const void *emb, const sru_weights *w, int B, int L, int dtype, int32_t *pred_idx,
+                           float *logits_opt, void *ws, size_t ws_bytes, void *stream)
+{
+    int rc = sru_check(w, B, L, dtype);
+    if (rc != MOE_OK) return rc;
+    MOE_REQUIRE(w->w_cat && w->w_head, MOE_ERR_INVALID_ARG, "sru_predict: null weight table");
+    for (int l = 0; l < w->n_layers; ++l)
+        MOE_REQUIRE(w->w_cat[l] && aligned16(w->w_cat[l]), MOE_ERR_INVALID_ARG,
+                    "sru_predict: w_cat[%d] null or misaligned", l);
+    if (B == 0) return MOE_OK;
+    MOE_REQUIRE(emb && pred_idx && aligned16(emb), MOE_ERR_INVALID_ARG, "sru_predict: null or misaligned pointer");
+    SruWs lay = sru_ws_layout(w, B, L);
+    MOE_REQUIRE(ws && aligned16(ws) && ws_bytes >= lay.total, MOE_ERR_WORKSPACE,
+                "sru_predict: workspace of %zu bytes needed, %zu given", lay.total, ws_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    char *base = (char *)ws;
+    float *U = (float *)(base + lay.u);
+    bf16_t *hbuf[2] = {(bf16_t *)(base + lay.h0), (bf16_t *)(base + lay.h1)};
+    void *wp = base + lay.wp;
+    const int T = B * L, n_h = w->n_hidden;
+    const bf16_t *cur = (const bf16_t *)emb;
+    int nin = w->n_in;
+    for (int l = 0; l < w->n_layers; ++l) {
+        int k = nin == n_h ? 3 : 4;
+        int ncol = k * n_h;
+        MOE_REQUIRE(ncol % 128 == 0, MOE_ERR_UNSUPPORTED, "sru_predict: %d*n_hidden must be a multiple of 128", k);
+        rc = pack_matrix_launch(w->w_cat[l], nin, ncol, wp, st, "sru_predict/pack");
+        if (rc != MOE_OK) return rc;
+        hipLaunchKernelGGL(sru_proj_kernel, dim3(ceil_div(T, 64) * (ncol / 128)), dim3(GEMM_THREADS), 0, st, cur,
+                           (const bf16_t *)wp, T, nin, ncol, U);
+        MOE_CHECK_LAUNCH("sru_predict/proj");
+        bf16_t *out = hbuf[l & 1];
+        hipLaunchKernelGGL(sru_scan_kernel, dim3(n_h / 64, B), dim3(64 * SRU_CHUNKS), 0, st, U, cur, L, n_h, k,
+                           w->b_f ? w->b_f[l] : nullptr, w->b_r ? w->b_r[l] : nullptr, out);
+        MOE_CHECK_LAUNCH("sru_predict/scan");
+        cur = out;
+        nin = n_h;
+    }
+    return route_launch(cur, w->w_head, w->b_head, T, n_h, w->n_out, MOE_BF16, pred_idx, (float *)(base + lay.prob),
+                        logits_opt, base + lay.rws, st, "sru_predict/head");
+}

@@ -1,0 +1,82 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, and
+rejects bad arguments on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2605_11537_amd as moe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "moe_mpmc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+char\s*\*|int|size_t)\s*\**\s*(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported():
+    L = moe.lib()
+    declared = _declared()
+    assert set(declared) == set(moe.EXPORTS), (declared, moe.EXPORTS)
+    for n in declared:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_error_text():
+    L = moe.lib()
+    assert L.moe_version() >= 100
+    assert isinstance(L.moe_last_error(), bytes)
+
+
+def test_workspace_queries():
+    L = moe.lib()
+    assert L.moe_route_workspace_bytes(4096, 768, 128, moe.MOE_BF16) >= 768 * 128 * 2
+    assert L.moe_dispatch_workspace_bytes(4096, 128) >= 4 * 128 * 4
+    assert L.moe_dispatch_workspace_bytes(-1, 128) == 0
+    assert L.moe_packed_weights_bytes(128, 768, 3072, moe.MOE_BF16) == 128 * 768 * 3072 * 2
+    assert L.moe_expert_ffn_workspace_bytes(4096, 144, 768, 3072, moe.MOE_BF16) >= 4096 * 3072 * 2
+
+
+def test_invalid_arguments_are_rejected_on_the_host():
+    L = moe.lib()
+    buf = (C.c_char * 4096)()
+    p = C.cast(buf, C.c_void_p)
+    INV, UNS, WS = -1, -2, -3
+    # moe_route
+    assert L.moe_route(p, p, None, -1, 64, 8, 0, p, p, None, p, 4096, None) == INV
+    assert L.moe_route(p, p, None, 4, 60, 8, 0, p, p, None, p, 4096, None) == INV       # d % 8
+    assert L.moe_route(None, p, None, 4, 64, 8, 0, p, p, None, p, 4096, None) == INV
+    assert L.moe_route(p, p, None, 4, 64, 8, 7, p, p, None, p, 4096, None) == INV       # dtype
+    assert L.moe_route(p, p, None, 4, 64, 2048, 0, p, p, None, p, 4096, None) == UNS
+    assert L.moe_route(p, p, None, 4, 768, 128, 1, p, p, None, p, 16, None) == WS
+    assert b"workspace" in L.moe_last_error()
+    # replica_plan
+    assert L.replica_plan(p, 4, 8, -1, 1, 0, p, p, p, p, p, None) == INV
+    assert L.replica_plan(p, 4, 8, 2, 0, 0, p, p, p, p, p, None) == INV
+    assert L.replica_plan(p, 4, 8, 2, 1, 3, p, p, p, p, p, None) == INV
+    assert L.replica_plan(p, 4, 4096, 2, 1, 0, p, p, p, p, p, None) == UNS
+    # moe_dispatch
+    assert L.moe_dispatch(p, p, None, 4, 64, 8, 0, 8, 0, p, p, p, p, p, p, p, p, 4096, None) == INV  # C = 0
+    assert L.moe_dispatch(p, p, None, 4, 6, 8, 1, 8, 0, p, p, p, p, p, p, p, p, 4096, None) == INV   # row bytes
+    assert L.moe_dispatch(p, p, None, 4, 64, 8, 1, 4, 0, p, p, p, p, p, p, p, p, 4096, None) == INV  # max_slots < E
+    assert L.moe_dispatch(p, p, None, 4, 64, 8, 1, 8, 0, p, p, p, p, p, p, p, None, 0, None) == WS
+    # moe_pack_weights / moe_expert_ffn
+    assert L.moe_pack_weights(p, 2, 12, 16, 1, p, None) == INV                       # K % 8 / aliasing
+    assert L.moe_pack_weights(p, 2, 16, 16, 0, p, None) == UNS
+    assert L.moe_expert_ffn(p, p, p, 0, p, p, p, 4, 8, 8, 768, 3072, 1, 0, p, p, 1 << 30, None) == UNS  # plain bf16
+    assert L.moe_expert_ffn(p, p, p, 1, p, p, p, 4, 8, 8, 100, 3072, 1, 0, p, p, 1 << 30, None) == UNS  # d % 128
+    assert L.moe_expert_ffn(p, p, p, 0, p, p, p, 4, 8, 8, 64, 256, 0, 5, p, p, 1 << 30, None) == INV   # schedule
+    assert L.moe_expert_ffn(p, p, p, 0, p, p, p, 4, 8, 8, 64, 256, 0, 0, p, p, 16, None) == WS
+    # moe_combine
+    assert L.moe_combine(p, p, p, p, 4, 64, 0, 2, p, None) == INV                     # residual flag
+    q = C.cast(C.addressof(buf) + 1024, C.c_void_p)
+    assert L.moe_combine(p, q, p, p, 4, 64, 0, 0, q, None) == INV                     # out aliases x
+    # sru_predict
+    w = moe.binding.SruWeightsC(2, 768, 256, 128, None, None, None, None, None)
+    assert L.sru_predict(p, C.byref(w), 8, 512, 0, p, None, p, 4096, None) == UNS   # fp32 not built
+    assert L.sru_predict(p, C.byref(w), 8, 512, 1, p, None, p, 4096, None) == INV   # null tables
+    assert L.sru_predict_workspace_bytes(C.byref(w), 8, 512, 1) > 8 * 512 * 1024 * 4
