@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the replicated top-1 MoE layer forward on one MI355X.
+
+A step = one pass of the whole layer path on one resident batch of synthetic tokens:
+moe_route -> replica_plan -> moe_dispatch -> moe_expert_ffn -> moe_combine (with --sru also
+sru_predict in front, its ids driving the plan).  Default workload: the Switch-base-128 shaped
+layer (T=4096, d=768, F=3072, E=128, capacity factor 1.25, replica budget 16, bf16 with fp32
+accumulation), Zipf(1.0)-skewed routing.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg4b|cfg5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def _to_dev(a):
+    import torch
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def _workload(name):
+    import synth
+    if name == "cfg2":
+        c = synth.config_inputs(2)
+        return c, c["C"], "Switch-base-128 layer T=4096 d=768 F=3072 E=128 CF=1.25 R=16 Zipf(1.0)"
+    if name == "cfg4":
+        c = synth.config_inputs(4)
+        return c, c["C"], "Switch-base-256 layer T=16384 d=768 F=3072 E=256 CF=1.0 R=32 Zipf(1.1)"
+    if name == "cfg4b":
+        c = synth.config_inputs(4)
+        return c, c["C_alt"], "Switch-base-256 layer T=16384 d=768 F=3072 E=256 CF=2.0 R=32 Zipf(1.1)"
+    if name == "cfg5":
+        c = synth.config_inputs(5)
+        c.update(c["layers"][0])
+        return c, c["C"], "extreme skew, one layer of the stack: T=65536 E=256 CF=4.0 R=64, 50% hot expert"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def _time_steps(step, steps):
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def _cpu_baseline(c, C, R, budget_s=20.0):
+    """The oracle as it stands, on the host cores: router, plan, dispatch and combine on the
+    whole batch, the expert FFN on a sample of kept rows sized to ~budget_s, scaled to K."""
+    import oracle
+    T, E = c["T"], c["E"]
+    t0 = time.perf_counter()
+    rt = oracle.route(c["x"], c["w_router"], c["b_router"])
+    pl = oracle.plan(rt["idx"], E, R, C)
+    dp = oracle.dispatch(c["x"], rt["idx"], pl["replicas"], E, C, E + R)
+    t_front = time.perf_counter() - t0
+    K = int(dp["expert_offset"][E])
+    rng = np.random.default_rng(0)
+    probe = np.sort(rng.choice(K, size=min(K, 32), replace=False)).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.ffn(dp["x_perm"], c["w1"], c["w2"], dp["slot_offset"], pl["slot_expert"], pl["n_slots"], rows=probe)
+    per_row = (time.perf_counter() - t0) / len(probe)
+    n = int(max(32, min(K, budget_s / max(per_row, 1e-9))))
+    rows = np.sort(rng.choice(K, size=n, replace=False)).astype(np.int32)
+    t0 = time.perf_counter()
+    y = oracle.ffn(dp["x_perm"], c["w1"], c["w2"], dp["slot_offset"], pl["slot_expert"], pl["n_slots"], rows=rows)
+    t_ffn = (time.perf_counter() - t0) * (K / n)
+    t0 = time.perf_counter()
+    oracle.combine(y, c["x"], dp["inv"], rt["prob"], 0)
+    t_back = time.perf_counter() - t0
+    total = t_front + t_ffn + t_back
+    return dict(value=T / total, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"router, plan, dispatch, combine on all {T} tokens; expert FFN on {n} of the {K} kept "
+                       f"rows, its time scaled by {K}/{n}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--modes", default="on,off_same_plan,off_budget0",
+                    help="replication modes to time besides 'on' (comma list)")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        raise SystemExit(2)
+
+    import torch
+    import paper_2605_11537_amd as moe
+    moe.lib()
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+
+    c, C, desc = _workload(a.workload)
+    T, d, F, E, R = c["T"], c["d"], c["F"], c["E"], c["R"]
+    dt = torch.bfloat16
+    x, wr, b = _to_dev(c["x"]), _to_dev(c["w_router"]), _to_dev(c["b_router"])
+    w1 = moe.moe_pack_weights(_to_dev(c["w1"]))
+    w2 = moe.moe_pack_weights(_to_dev(c["w2"]))
+    torch.cuda.synchronize()
+
+    layer = moe.MoeLayer(T, d, F, E, R, C, dt)
+    layer0 = moe.MoeLayer(T, d, F, E, 0, C, dt)          # budget 0: the plain Switch layer
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
+    for trio in evs:
+        for e in trio:
+            e.record()                                   # creates the underlying hipEvent
+    it = {"i": 0, "timed": False}
+
+    def step_on():
+        if it["timed"]:
+            moe.set_ffn_timing_events(*evs[it["i"]])
+            it["i"] += 1
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS)
+
+    def step_off_same_plan():
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS)
+
+    def step_off_budget0():
+        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS)
+
+    for _ in range(a.warmup):
+        step_on()
+    it["timed"] = True
+    ms_on = _time_steps(step_on, a.steps)
+    it["timed"] = False
+    g1 = float(np.mean([t[0].elapsed_time(t[1]) for t in evs]))
+    g2 = float(np.mean([t[1].elapsed_time(t[2]) for t in evs]))
+
+    kept = layer.disp_out["kept"].cpu().numpy()
+    K = int(kept.sum())
+    active = int((kept > 0).sum())
+    n_slots = int(layer.plan_out["n_slots"].item())
+    esz = 2
+    bytes_g1 = active * d * F * esz + K * d * esz + K * F * esz
+    bytes_g2 = active * F * d * esz + K * F * esz + K * d * esz
+    flops = 2.0 * K * d * F
+    dom = ("ffn_gemm1", g1, bytes_g1) if g1 >= g2 else ("ffn_gemm2", g2, bytes_g2)
+    ach = dom[2] / (dom[1] * 1e-3) / 1e9
+    roofline = dict(bound="hbm", kernel=dom[0], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=None,
+                    avg_ms=round(dom[1], 5), algorithmic_bytes=int(dom[2]),
+                    ffn_gemm1_ms=round(g1, 5), ffn_gemm2_ms=round(g2, 5),
+                    ffn_mfma_tflops=round(2 * flops / ((g1 + g2) * 1e-3) / 1e12, 2),
+                    ffn_mfma_frac_of_bf16_peak=round(2 * flops / ((g1 + g2) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4))
+
+    modes = {"on": round(T / (ms_on * 1e-3), 1)}
+    extra_ms = {"on": round(ms_on, 5)}
+    for name, fn in (("off_same_plan", step_off_same_plan), ("off_budget0", step_off_budget0)):
+        if name in a.modes.split(","):
+            for _ in range(max(2, a.warmup // 2)):
+                fn()
+            ms = _time_steps(fn, max(10, a.steps // 2))
+            modes[name] = round(T / (ms * 1e-3), 1)
+            extra_ms[name] = round(ms, 5)
+    kept0 = int(layer0.disp_out["kept"].sum().item()) if "off_budget0" in modes else None
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = _cpu_baseline(c, C, R)
+        cpu["value"] = round(cpu["value"], 1)
+
+    line = {
+        "metric": "MoE-layer tokens/sec (route+dispatch+FFN+combine)", "value": modes["on"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_on, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": desc, "name": a.workload, "T": T, "d_model": d, "d_ff": F, "experts": E,
+                   "slot_capacity": C, "replica_budget": R, "kept_tokens": K, "active_experts": active,
+                   "slots": n_slots, "replication": "on (slot schedule)"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "replication_modes_tokens_per_s": modes,
+        "replication_modes_ms": extra_ms,
+        "kept_tokens_budget0": kept0,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

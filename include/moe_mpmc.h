@@ -83,8 +83,9 @@ int moe_route(const void *x, const void *w_router, const float *b_router, int T,
  * when n_in_l != n_hidden (k_l = 4), W_h; n_in_0 = n_in, n_in_l = n_hidden afterwards.
  * b_f / b_r: arrays of n_layers device pointers to [n_hidden] binary32, or NULL (all zero);
  * single entries may be NULL too.  w_head [n_hidden, n_out]; b_head [n_out] or NULL.
- * emb [B, L, n_in].  Only MOE_BF16 is built; n_in and n_hidden multiples of 64, n_out a
- * multiple of 128 and <= 256.  Layer outputs are stored as bfloat16 between layers.
+ * emb [B, L, n_in].  Only MOE_BF16 is built; n_in a multiple of 64, n_hidden a multiple of
+ * 128, n_out a multiple of 8 and <= MOE_MAX_EXPERTS.  Layer outputs are stored as bfloat16
+ * between layers.
  */
 typedef struct sru_weights {
     int n_layers, n_in, n_hidden, n_out;
@@ -171,6 +172,12 @@ int moe_expert_ffn(const void *x_perm, const void *w1, const void *w2, int weigh
                    const int32_t *slot_offset, const int32_t *slot_expert, const int32_t *n_slots,
                    int max_rows, int max_slots, int E, int d, int F, int dtype, int schedule,
                    void *y_perm, void *ws, size_t ws_bytes, void *stream);
+
+/* Measurement hook (not part of the method): the next moe_expert_ffn call made by this host
+ * thread records the three hipEvent_t handles (passed as void*, any may be NULL) on its
+ * stream: before its first GEMM kernel, between the two GEMM kernels, after the second.  The
+ * handles are forgotten after that call. */
+int moe_expert_ffn_set_timing_events(void *before_gemm1, void *between, void *after_gemm2);
 
 /* ---------------------------------------------------------------------------------------
  * moe_combine -- expert output scaled by the gate probability, back in token order; tokens

@@ -21,4 +21,5 @@ from .binding import (  # noqa: F401
     moe_route,
     replica_plan,
     sru_predict,
+    set_ffn_timing_events,
 )

@@ -25,7 +25,7 @@ EXPORTS = (
     "replica_plan",
     "moe_dispatch_workspace_bytes", "moe_dispatch",
     "moe_packed_weights_bytes", "moe_pack_weights",
-    "moe_expert_ffn_workspace_bytes", "moe_expert_ffn",
+    "moe_expert_ffn_workspace_bytes", "moe_expert_ffn", "moe_expert_ffn_set_timing_events",
     "moe_combine",
 )
 
@@ -69,6 +69,7 @@ def lib():
         _lib.moe_pack_weights.argtypes = [P, I, I, I, I, P, P]
         _lib.moe_expert_ffn_workspace_bytes.argtypes = [I, I, I, I, I]
         _lib.moe_expert_ffn.argtypes = [P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P]
+        _lib.moe_expert_ffn_set_timing_events.argtypes = [P, P, P]
         _lib.moe_combine.argtypes = [P, P, P, P, I, I, I, I, P, P]
     return _lib
 
@@ -209,6 +210,13 @@ def moe_expert_ffn(x_perm, w1, w2, slot_offset, slot_expert, n_slots, E, F, max_
                                 _ptr(slot_expert), _ptr(n_slots), max_rows, max_slots, E, d, F, dt, schedule,
                                 _ptr(y), _ptr(ws), ws.numel(), _stream()))
     return y
+
+
+def set_ffn_timing_events(ev0, ev1, ev2):
+    """torch.cuda.Event objects (enable_timing=True, already created by a first record()) that the
+    next moe_expert_ffn call records around its two GEMM kernels."""
+    _check(lib().moe_expert_ffn_set_timing_events(C.c_void_p(ev0.cuda_event), C.c_void_p(ev1.cuda_event),
+                                                  C.c_void_p(ev2.cuda_event)))
 
 
 def moe_combine(y_perm, x, inv, expert_prob, residual=0, out=None):

@@ -191,6 +191,9 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restri
 
 static inline int ffn_max_items(int max_rows, int max_slots) { return max_slots + max_rows / FFN_BM + 1; }
 
+// events the next moe_expert_ffn call of this thread records around its two GEMM kernels
+static thread_local hipEvent_t g_timing_ev[3] = {nullptr, nullptr, nullptr};
+
 }  // namespace moe
 
 using namespace moe;
@@ -212,6 +215,14 @@ extern "C" int moe_pack_weights(const void *w, int E, int K, int N, int dtype, v
     hipLaunchKernelGGL(pack_weights_kernel, dim3(ceil_div(N, 256), K / 8, E), dim3(256), 0, (hipStream_t)stream,
                        (const bf16_t *)w, K, N, (uint4 *)w_packed);
     MOE_CHECK_LAUNCH("moe_pack_weights");
+    return MOE_OK;
+}
+
+extern "C" int moe_expert_ffn_set_timing_events(void *before_gemm1, void *between, void *after_gemm2)
+{
+    g_timing_ev[0] = (hipEvent_t)before_gemm1;
+    g_timing_ev[1] = (hipEvent_t)between;
+    g_timing_ev[2] = (hipEvent_t)after_gemm2;
     return MOE_OK;
 }
 
@@ -273,12 +284,16 @@ extern "C" int moe_expert_ffn(const void *x_perm, const void *w1, const void *w2
                        max_items, schedule, items, n_items);
     MOE_CHECK_LAUNCH("moe_expert_ffn/worklist");
     int grid_items = schedule == MOE_SCHEDULE_SLOTS ? max_items : (max_slots < max_items ? max_slots : max_items);
+    hipEvent_t ev[3] = {g_timing_ev[0], g_timing_ev[1], g_timing_ev[2]};
+    g_timing_ev[0] = g_timing_ev[1] = g_timing_ev[2] = nullptr;
+    if (ev[0]) (void)hipEventRecord(ev[0], st);
     if (dtype == MOE_BF16) {
         int g1 = (int)align_up((size_t)grid_items * (F / FFN_BN), 8);
         int g2 = (int)align_up((size_t)grid_items * (d / FFN_BN), 8);
         hipLaunchKernelGGL(ffn_gemm_bf16_kernel<true>, dim3(g1), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x_perm,
                            (const bf16_t *)w1, d, F, E, items, n_items, max_rows, (bf16_t *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
+        if (ev[1]) (void)hipEventRecord(ev[1], st);
         hipLaunchKernelGGL(ffn_gemm_bf16_kernel<false>, dim3(g2), dim3(GEMM_THREADS), 0, st, (const bf16_t *)h,
                            (const bf16_t *)w2, F, d, E, items, n_items, max_rows, (bf16_t *)y_perm);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm2");
@@ -287,9 +302,11 @@ extern "C" int moe_expert_ffn(const void *x_perm, const void *w1, const void *w2
         hipLaunchKernelGGL(ffn_gemm_f32_kernel<true>, dim3(g1), dim3(256), 0, st, (const float *)x_perm,
                            (const float *)w1, d, F, E, items, n_items, max_rows, (float *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
+        if (ev[1]) (void)hipEventRecord(ev[1], st);
         hipLaunchKernelGGL(ffn_gemm_f32_kernel<false>, dim3(g2), dim3(256), 0, st, (const float *)h,
                            (const float *)w2, F, d, E, items, n_items, max_rows, (float *)y_perm);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm2");
     }
+    if (ev[2]) (void)hipEventRecord(ev[2], st);
     return MOE_OK;
 }

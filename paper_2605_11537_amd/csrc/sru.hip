@@ -121,8 +121,8 @@ static int sru_check(const sru_weights *w, int B, int L, int dtype)
                 w->n_layers, w->n_in, w->n_hidden, w->n_out);
     MOE_REQUIRE((long long)B * L <= 0x7fffffffLL / 4096, MOE_ERR_UNSUPPORTED, "sru_predict: B*L too large");
     MOE_REQUIRE(dtype == MOE_BF16, MOE_ERR_UNSUPPORTED, "sru_predict: only MOE_BF16 is built");
-    MOE_REQUIRE(w->n_in % 64 == 0 && w->n_hidden % 64 == 0, MOE_ERR_UNSUPPORTED,
-                "sru_predict: n_in=%d and n_hidden=%d must be multiples of 64", w->n_in, w->n_hidden);
+    MOE_REQUIRE(w->n_in % 64 == 0 && w->n_hidden % 128 == 0, MOE_ERR_UNSUPPORTED,
+                "sru_predict: n_in=%d must be a multiple of 64 and n_hidden=%d of 128", w->n_in, w->n_hidden);
     MOE_REQUIRE(w->n_out <= MOE_MAX_EXPERTS && w->n_out % 8 == 0, MOE_ERR_UNSUPPORTED,
                 "sru_predict: n_out=%d must be a multiple of 8 and at most %d", w->n_out, MOE_MAX_EXPERTS);
     MOE_REQUIRE(B <= 65535, MOE_ERR_UNSUPPORTED, "sru_predict: B=%d exceeds 65535", B);
@@ -164,7 +164,6 @@ extern "C" int sru_predict(const void *emb, const sru_weights *w, int B, int L, 
     for (int l = 0; l < w->n_layers; ++l) {
         int k = nin == n_h ? 3 : 4;
         int ncol = k * n_h;
-        MOE_REQUIRE(ncol % 128 == 0, MOE_ERR_UNSUPPORTED, "sru_predict: %d*n_hidden must be a multiple of 128", k);
         rc = pack_matrix_launch(w->w_cat[l], nin, ncol, wp, st, "sru_predict/pack");
         if (rc != MOE_OK) return rc;
         hipLaunchKernelGGL(sru_proj_kernel, dim3(ceil_div(T, 64) * (ncol / 128)), dim3(GEMM_THREADS), 0, st, cur,
