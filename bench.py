@@ -115,7 +115,9 @@ def main():
     c, C, desc = _workload(a.workload)
     T, d, F, E, R = c["T"], c["d"], c["F"], c["E"], c["R"]
     dt = torch.bfloat16
-    x, wr, b = _to_dev(c["x"]), _to_dev(c["w_router"]), _to_dev(c["b_router"])
+    x, b = _to_dev(c["x"]), _to_dev(c["b_router"])
+    # static weights are packed once, outside the timed region (router included)
+    wr = moe.moe_pack_weights(_to_dev(c["w_router"])[None].contiguous())[0]
     w1 = moe.moe_pack_weights(_to_dev(c["w1"]))
     w2 = moe.moe_pack_weights(_to_dev(c["w2"]))
     torch.cuda.synchronize()
@@ -132,18 +134,22 @@ def main():
         if it["timed"]:
             moe.set_ffn_timing_events(*evs[it["i"]])
             it["i"] += 1
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS)
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED)
 
     def step_off_same_plan():
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS)
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=moe.LAYOUT_PACKED)
 
     def step_off_budget0():
-        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS)
+        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED)
 
     for _ in range(a.warmup):
         step_on()
+    ms_on = _time_steps(step_on, a.steps)           # headline: K clean steps
+    # second pass over the same K steps, the two FFN GEMM kernels bracketed by HIP events on the
+    # launch stream (recording an event between kernels costs a few us, so it is kept out of the
+    # headline pass)
     it["timed"] = True
-    ms_on = _time_steps(step_on, a.steps)
+    ms_on_events = _time_steps(step_on, a.steps)
     it["timed"] = False
     g1 = float(np.mean([t[0].elapsed_time(t[1]) for t in evs]))
     g2 = float(np.mean([t[1].elapsed_time(t[2]) for t in evs]))
@@ -192,6 +198,7 @@ def main():
         "cpu_baseline": cpu,
         "replication_modes_tokens_per_s": modes,
         "replication_modes_ms": extra_ms,
+        "ms_per_step_with_kernel_events": round(ms_on_events, 5),
         "kept_tokens_budget0": kept0,
     }
     print(json.dumps(line))

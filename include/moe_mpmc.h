@@ -62,11 +62,14 @@ int moe_version(void);
  *   expert_prob[s] = softmax(logit[s])[expert_idx[s]]
  * x [T,d]; w_router [d,E]; b_router [E] binary32 or NULL (= 0); logits_opt [T,E] binary32
  * or NULL.  Sums, exponentials and the argmax are taken in binary32 for both dtypes.
+ * w_layout: MOE_LAYOUT_PLAIN = row-major [d,E] (re-laid into the workspace on every call), or
+ * MOE_LAYOUT_PACKED = the image moe_pack_weights writes for a [1,d,E] tensor (static router
+ * weights packed once; bf16 with E = 128 or 256 and d a multiple of 128 only).
  * d must be a multiple of 8.  T = 0 is a no-op.
  */
 size_t moe_route_workspace_bytes(int T, int d, int E, int dtype);
-int moe_route(const void *x, const void *w_router, const float *b_router, int T, int d, int E,
-              int dtype, int32_t *expert_idx, float *expert_prob, float *logits_opt, void *ws,
+int moe_route(const void *x, const void *w_router, int w_layout, const float *b_router, int T, int d,
+              int E, int dtype, int32_t *expert_idx, float *expert_prob, float *logits_opt, void *ws,
               size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
@@ -147,7 +150,10 @@ int moe_dispatch(const void *x, const int32_t *expert_idx, const int32_t *replic
 /* ---------------------------------------------------------------------------------------
  * moe_pack_weights -- one-time re-layout of static expert weights for the bf16 matrix-core
  * kernels (inference weights do not change between batches).  Input w [E, K, N] row-major
- * bf16; output element ((e*(K/8) + k/8)*N + n)*8 + k%8 = w[e][k][n].  K a multiple of 8.
+ * bf16, K a multiple of 8, N a multiple of 32.  Output, in 16-byte pieces of 8 consecutive k:
+ * piece ((e*(N/32) + n/32)*(K/8) + k/8)*32 + n%32 holds w[e][8*(k/8) .. 8*(k/8)+7][n], i.e.
+ * columns are grouped in strips of 32 and a strip is stored front to back along k, so a
+ * wavefront that owns a strip streams it from HBM in address order.
  * moe_packed_weights_bytes gives the output size (equal to the input size).
  */
 size_t moe_packed_weights_bytes(int E, int K, int N, int dtype);

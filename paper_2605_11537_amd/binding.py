@@ -59,7 +59,7 @@ def lib():
                 f.restype = C.c_int
         I, S, P = C.c_int, C.c_size_t, C.c_void_p
         _lib.moe_route_workspace_bytes.argtypes = [I, I, I, I]
-        _lib.moe_route.argtypes = [P, P, P, I, I, I, I, P, P, P, P, S, P]
+        _lib.moe_route.argtypes = [P, P, I, P, I, I, I, I, P, P, P, P, S, P]
         _lib.sru_predict_workspace_bytes.argtypes = [C.POINTER(SruWeightsC), I, I, I]
         _lib.sru_predict.argtypes = [P, C.POINTER(SruWeightsC), I, I, I, P, P, P, S, P]
         _lib.replica_plan.argtypes = [P, I, I, I, I, I, P, P, P, P, P, P]
@@ -107,8 +107,9 @@ def _ws(nbytes, dev):
 
 
 # --------------------------------------------------------------------------- the calls
-def moe_route(x, w_router, b_router=None, want_logits=False, out=None, ws=None):
-    """-> (expert_idx int32[T], expert_prob f32[T], logits f32[T,E] or None)."""
+def moe_route(x, w_router, b_router=None, want_logits=False, out=None, ws=None, w_layout=LAYOUT_PLAIN):
+    """-> (expert_idx int32[T], expert_prob f32[T], logits f32[T,E] or None).  w_router is [d,E];
+    with w_layout=LAYOUT_PACKED it is the image ``moe_pack_weights(w_router[None])[0]``."""
     T, d = x.shape
     E = w_router.shape[1]
     dev = x.device
@@ -118,7 +119,7 @@ def moe_route(x, w_router, b_router=None, want_logits=False, out=None, ws=None):
     logits = torch.empty(T, E, dtype=torch.float32, device=dev) if want_logits else None
     need = lib().moe_route_workspace_bytes(T, d, E, dt)
     ws = ws if ws is not None else _ws(need, dev)
-    _check(lib().moe_route(_ptr(x), _ptr(w_router), _ptr(b_router), T, d, E, dt, _ptr(idx), _ptr(prob),
+    _check(lib().moe_route(_ptr(x), _ptr(w_router), w_layout, _ptr(b_router), T, d, E, dt, _ptr(idx), _ptr(prob),
                            _ptr(logits), _ptr(ws), ws.numel(), _stream()))
     return idx, prob, logits
 
@@ -252,8 +253,9 @@ class MoeLayer:
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
 
     def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
-                out=None, budget=None):
-        idx, prob, _ = moe_route(x, w_router, b_router, out=self.route_out, ws=self.route_ws)
+                out=None, budget=None, router_layout=LAYOUT_PLAIN):
+        idx, prob, _ = moe_route(x, w_router, b_router, out=self.route_out, ws=self.route_ws,
+                                 w_layout=router_layout)
         R = self.R if budget is None else budget
         if R != self.R:
             raise ValueError("budget is fixed by the preallocated slot tables")

@@ -53,15 +53,17 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
-// XCD-aware remap of a linear workgroup id: hardware deals consecutive workgroup ids to the 8
-// XCDs in turn, so ids that are congruent mod 8 share an L2.  The remap gives each XCD a
-// contiguous range of logical ids, so that neighbours in the logical order (which share
-// operands) meet in one L2.  Needs gridDim.x to be a multiple of 8 to be a bijection; the
-// caller pads the grid and idle ids exit.
-__device__ __forceinline__ int xcd_remap(int bid, int grid)
+// XCD-aware remap of a linear workgroup id.  Hardware deals consecutive workgroup ids to the
+// 8 XCDs in turn, so ids congruent mod 8 share an L2.  The n_valid units of work are cut into 8
+// contiguous ranges, one per XCD: neighbours in the logical order (which share operands) meet
+// in one L2, and every XCD gets the same share even when the grid was sized for a worst case
+// larger than n_valid.  Returns -1 for a workgroup with nothing to do.
+__device__ __forceinline__ int xcd_remap(int bid, int n_valid)
 {
-    int per = grid >> 3;
-    return (bid & 7) * per + (bid >> 3);
+    int per = (n_valid + 7) >> 3;
+    int slot = bid >> 3;
+    int lid = (bid & 7) * per + slot;
+    return (slot < per && lid < n_valid) ? lid : -1;
 }
 
 // Exclusive scan of one int per thread over a 1024-thread workgroup.  Returns the prefix and

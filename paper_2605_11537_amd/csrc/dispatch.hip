@@ -3,12 +3,13 @@
 // Three kernels, no global atomics, so the permutation is the stable one whatever the
 // hardware scheduling:
 //   hist     one workgroup per 1024 tokens: LDS histogram of expert ids -> block_hist[b][e]
-//   scan     one workgroup: per expert, exclusive prefix over the token blocks; kept counts,
-//            expert offsets (scan over experts), slot offsets (balanced split per expert)
-//   permute  one workgroup per 1024 tokens: rank of every token among the tokens of its expert
+//   permute  one workgroup per 1024 tokens: per expert, prefix over the earlier token blocks,
+//            kept counts, expert offsets (scan over experts), slot offsets (balanced split
+//            per expert); then the rank of every token among the tokens of its expert
 //            = prefix over earlier blocks + prefix over earlier 64-token chunks of the block
 //            (LDS table) + rank inside the chunk (wavefront ballots, one per id bit);
-//            writes inv / perm and copies the kept rows with 16-byte accesses.
+//            writes inv / perm
+//   gather   whole-chip copy of the kept rows, x_perm[pos] = x[perm[pos]], 16-byte accesses
 #include "common.h"
 
 namespace moe {
@@ -36,62 +37,109 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_hist_kernel(const int32_
     for (int e = threadIdx.x; e < E; e += DSP_THREADS) block_hist[(size_t)blockIdx.x * E + e] = hist[e];
 }
 
-__global__ __launch_bounds__(1024) void dispatch_scan_kernel(int32_t *__restrict__ block_hist, int nb, int E,
-                                                              const int32_t *__restrict__ replicas, int C,
-                                                              int max_slots, int32_t *__restrict__ counts,
-                                                              int32_t *__restrict__ kept,
-                                                              int32_t *__restrict__ expert_offset,
-                                                              int32_t *__restrict__ slot_offset)
+// exclusive scan over E <= 1024 values held 4 per thread (thread t owns experts 4t .. 4t+3)
+__device__ __forceinline__ void block_scan4_256(const int (&v)[4], int (&excl)[4], int *wave_sums, int *total_out)
 {
-    __shared__ int wave_sums[16];
-    __shared__ int total_k, total_p;
-    int e = threadIdx.x;
-    int n = 0, r = 0, kp = 0;
-    if (e < E) {
-        for (int b = 0; b < nb; ++b) {
-            int v = block_hist[(size_t)b * E + e];
-            block_hist[(size_t)b * E + e] = n;
-            n += v;
-        }
-        r = replicas ? replicas[e] : 1;
-        if (r < 1) r = 1;
-        long long cap = (long long)r * C;
-        kp = (long long)n < cap ? n : (int)cap;
-        counts[e] = n;
-        kept[e] = kp;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int local = v[0] + v[1] + v[2] + v[3];
+    int inc = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int n = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += n;
     }
-    int off = block_scan_excl_1024(kp, wave_sums, &total_k);
-    int sb = block_scan_excl_1024(r, wave_sums, &total_p);
-    int K = total_k, P = total_p;
-    if (e < E) {
-        expert_offset[e] = off;
-        if (slot_offset) {
-            int q = kp / r, rem = kp % r;
-            for (int k = 0; k < r; ++k) {
-                int p = sb + k;
-                if (p <= max_slots) slot_offset[p] = off + k * q + (k < rem ? k : rem);
-            }
-        }
+    if (lane == 63) wave_sums[w] = inc;
+    __syncthreads();
+    int base = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) base += i < w ? wave_sums[i] : 0;
+    if (threadIdx.x == DSP_THREADS - 1) *total_out = base + inc;
+    int run = base + inc - local;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        excl[i] = run;
+        run += v[i];
     }
-    if (e == 0) expert_offset[E] = K;
-    if (slot_offset)
-        for (int p = P + e; p <= max_slots; p += 1024) slot_offset[p] = K;
+    __syncthreads();
 }
 
-template <typename VecT>
+// One workgroup per 1024 tokens.  Every workgroup first rebuilds, from the per-block
+// histograms, the per-expert totals, its own prefix over earlier blocks, the kept counts and
+// the expert offsets (a few KB of reads; cheaper than a separate single-workgroup launch in
+// the dependency chain); workgroup 0 also writes those tables and the slot offsets out.
 __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
-    const VecT *__restrict__ x, const int32_t *__restrict__ idx, const int32_t *__restrict__ replicas, int T,
-    int vec_per_row, int E, int nbits, int C, const int32_t *__restrict__ block_base,
-    const int32_t *__restrict__ expert_offset, int32_t *__restrict__ perm, int32_t *__restrict__ inv,
-    VecT *__restrict__ x_perm)
+    const int32_t *__restrict__ idx, const int32_t *__restrict__ replicas, int T, int E, int nbits, int C, int nb,
+    int max_slots, const int32_t *__restrict__ block_hist, int32_t *__restrict__ counts, int32_t *__restrict__ kept,
+    int32_t *__restrict__ expert_offset, int32_t *__restrict__ slot_offset, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv)
 {
     __shared__ unsigned short chunk_cnt[DSP_CHUNKS][MOE_MAX_EXPERTS];
-    __shared__ int dest_of[DSP_TOKENS];
+    __shared__ int before_e[MOE_MAX_EXPERTS];   // tokens of e in earlier blocks
+    __shared__ int eoff_e[MOE_MAX_EXPERTS];     // first permuted row of e
+    __shared__ int cap_e[MOE_MAX_EXPERTS];      // kept count of e
+    __shared__ int wave_sums[4];
+    __shared__ int total_k, total_p;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int base = blockIdx.x * DSP_TOKENS;
     for (int i = tid; i < DSP_CHUNKS * E; i += DSP_THREADS) chunk_cnt[i / E][i % E] = 0;
-    __syncthreads();
 
+    // ---- tables (thread t owns experts 4t..4t+3)
+    int n4[4], r4[4], k4[4], off4[4], sb4[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int e = tid * 4 + i;
+        int tot = 0, bef = 0;
+        if (e < E) {
+            for (int b = 0; b < nb; ++b) {
+                int v = block_hist[(size_t)b * E + e];
+                bef += b < (int)blockIdx.x ? v : 0;
+                tot += v;
+            }
+        }
+        int r = (e < E) ? (replicas ? replicas[e] : 1) : 0;
+        if (e < E && r < 1) r = 1;
+        long long cap = (long long)r * C;
+        n4[i] = tot;
+        r4[i] = r;
+        k4[i] = (long long)tot < cap ? tot : (int)cap;
+        if (e < E) {
+            before_e[e] = bef;
+            cap_e[e] = k4[i];
+        }
+    }
+    block_scan4_256(k4, off4, wave_sums, &total_k);
+    block_scan4_256(r4, sb4, wave_sums, &total_p);
+    const int K = total_k, P = total_p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int e = tid * 4 + i;
+        if (e < E) eoff_e[e] = off4[i];
+    }
+    if (blockIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int e = tid * 4 + i;
+            if (e < E) {
+                counts[e] = n4[i];
+                kept[e] = k4[i];
+                expert_offset[e] = off4[i];
+                if (slot_offset) {
+                    int q = k4[i] / r4[i], rem = k4[i] % r4[i];
+                    for (int k = 0; k < r4[i]; ++k) {
+                        int p = sb4[i] + k;
+                        if (p <= max_slots) slot_offset[p] = off4[i] + k * q + (k < rem ? k : rem);
+                    }
+                }
+            }
+        }
+        if (tid == 0) expert_offset[E] = K;
+        if (slot_offset)
+            for (int p = P + tid; p <= max_slots; p += DSP_THREADS) slot_offset[p] = K;
+    }
+    __syncthreads();
+    if (T == 0) return;
+
+    // ---- ranks inside the block
     int my_e[4], my_rank[4];
 #pragma unroll
     for (int rd = 0; rd < 4; ++rd) {
@@ -122,7 +170,6 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
         }
     }
     __syncthreads();
-    const int K = expert_offset[E];
 #pragma unroll
     for (int rd = 0; rd < 4; ++rd) {
         int c = rd * 4 + w;
@@ -130,42 +177,46 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
         int dest = -1;
         int e = my_e[rd];
         if (e >= 0) {
-            int j = block_base[(size_t)blockIdx.x * E + e] + chunk_cnt[c][e] + my_rank[rd];
-            int r = replicas ? replicas[e] : 1;
-            if (r < 1) r = 1;
-            long long cap = (long long)r * C;
-            if ((long long)j < cap) dest = expert_offset[e] + j;
+            int j = before_e[e] + chunk_cnt[c][e] + my_rank[rd];
+            if (j < cap_e[e]) dest = eoff_e[e] + j;
         }
-        dest_of[c * WAVE + lane] = dest;
         if (t < T) {
             inv[t] = dest;
             if (dest >= 0) perm[dest] = t;
             if (t >= K) perm[t] = -1;
         }
     }
-    __syncthreads();
-    if (!x) return;
-    int rows = T - base < DSP_TOKENS ? T - base : DSP_TOKENS;
-    int total = rows * vec_per_row;
-    const VecT *src = x + (size_t)base * vec_per_row;
-    for (int i = tid; i < total; i += DSP_THREADS * 4) {
-        VecT v[4];
-        int dst[4], col[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            int ii = i + u * DSP_THREADS;
-            dst[u] = -1;
-            if (ii < total) {
-                int row = ii / vec_per_row;
-                col[u] = ii - row * vec_per_row;
-                dst[u] = dest_of[row];
-                if (dst[u] >= 0) v[u] = src[ii];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (dst[u] >= 0) x_perm[(size_t)dst[u] * vec_per_row + col[u]] = v[u];
+}
+
+// x_perm[pos] = x[perm[pos]] for pos < K.  32 lanes per row, 8 rows per workgroup, 16-byte
+// pieces: the scattered row reads and the contiguous writes are both whole lines, the row
+// index is read once per row, and all of a lane's loads are independent.
+constexpr int GATHER_ROWS = DSP_THREADS / 32;
+__global__ __launch_bounds__(DSP_THREADS) void dispatch_gather_kernel(const uint4 *__restrict__ x,
+                                                                      const int32_t *__restrict__ perm,
+                                                                      const int32_t *__restrict__ expert_offset, int E,
+                                                                      int vec_per_row, uint4 *__restrict__ x_perm)
+{
+    const int pos = blockIdx.x * GATHER_ROWS + (threadIdx.x >> 5);
+    const int l = threadIdx.x & 31;
+    if (pos >= expert_offset[E]) return;
+    const uint4 *src = x + (size_t)perm[pos] * vec_per_row;
+    uint4 *dst = x_perm + (size_t)pos * vec_per_row;
+    int c = l;
+    for (; c + 96 < vec_per_row; c += 128) {
+        uint4 v0 = src[c], v1 = src[c + 32], v2 = src[c + 64], v3 = src[c + 96];
+        dst[c] = v0;
+        dst[c + 32] = v1;
+        dst[c + 64] = v2;
+        dst[c + 96] = v3;
     }
+    uint4 v[3];
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+        if (c + u * 32 < vec_per_row) v[u] = src[c + u * 32];
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+        if (c + u * 32 < vec_per_row) dst[c + u * 32] = v[u];
 }
 
 }  // namespace moe
@@ -211,17 +262,20 @@ extern "C" int moe_dispatch(const void *x, const int32_t *expert_idx, const int3
         hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nb), dim3(DSP_THREADS), 0, st, expert_idx, T, E, block_hist);
         MOE_CHECK_LAUNCH("moe_dispatch/hist");
     }
-    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), 0, st, block_hist, nb, E, replicas,
-                       slot_capacity, max_slots, counts, kept, expert_offset, slot_offset);
-    MOE_CHECK_LAUNCH("moe_dispatch/scan");
-    if (nb > 0) {
+    {
         int nbits = 0;
         while ((1 << nbits) < E) ++nbits;
-        int vec_per_row = (int)((size_t)d * esz / 16);
-        hipLaunchKernelGGL(dispatch_permute_kernel<uint4>, dim3(nb), dim3(DSP_THREADS), 0, st, (const uint4 *)x,
-                           expert_idx, replicas, T, vec_per_row, E, nbits, slot_capacity, block_hist,
-                           expert_offset, perm, inv, (uint4 *)x_perm);
+        hipLaunchKernelGGL(dispatch_permute_kernel, dim3(nb > 0 ? nb : 1), dim3(DSP_THREADS), 0, st, expert_idx,
+                           replicas, T, E, nbits, slot_capacity, nb, max_slots, block_hist, counts, kept,
+                           expert_offset, slot_offset, perm, inv);
         MOE_CHECK_LAUNCH("moe_dispatch/permute");
+        if (x && nb > 0) {
+            int vec_per_row = (int)((size_t)d * esz / 16);
+            int grid = ceil_div(T, GATHER_ROWS);
+            hipLaunchKernelGGL(dispatch_gather_kernel, dim3(grid), dim3(DSP_THREADS), 0, st, (const uint4 *)x, perm,
+                               expert_offset, E, vec_per_row, (uint4 *)x_perm);
+            MOE_CHECK_LAUNCH("moe_dispatch/gather");
+        }
     }
     return MOE_OK;
 }

@@ -17,13 +17,14 @@ namespace moe {
 
 constexpr int FFN_BM = 64;    // rows per tile
 constexpr int FFN_BN = 128;   // columns per workgroup (bf16 path)
+constexpr int FFN_BK = 128;   // k chunk of the bf16 path
 
 struct __attribute__((aligned(16))) WorkItem {
     int expert, row_begin, row_end, pad;
 };
 
 // ------------------------------------------------------------------ weight packing
-// out[((e*(K/8) + k/8)*N + n)*8 + k%8] = in[e][k][n]
+// 16-byte piece (((e*(N/32) + n/32)*(K/8) + k/8)*32 + n%32) = in[e][8*(k/8) .. +7][n]
 __global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restrict__ in, int K, int N,
                                                            uint4 *__restrict__ out)
 {
@@ -35,7 +36,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restr
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         v[j] = (uint32_t)src[(size_t)(2 * j) * N] | ((uint32_t)src[(size_t)(2 * j + 1) * N] << 16);
-    out[((size_t)e * (K / 8) + kg) * N + n] = make_uint4(v[0], v[1], v[2], v[3]);
+    out[(((size_t)e * (N / 32) + (n >> 5)) * (K / 8) + kg) * 32 + (n & 31)] = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
 // ------------------------------------------------------------------ work list
@@ -95,11 +96,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
     const bf16_t *__restrict__ A, const bf16_t *__restrict__ Wp, int K, int N, int E,
     const WorkItem *__restrict__ items, const int32_t *__restrict__ n_items, int max_rows, bf16_t *__restrict__ C)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2>()];
+    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2, FFN_BK>()];
     const int n_nt = N / FFN_BN;
-    const int lid = xcd_remap(blockIdx.x, gridDim.x);
+    const int lid = xcd_remap(blockIdx.x, n_items[0] * n_nt);
+    if (lid < 0) return;
     const int item = lid / n_nt, nt = lid - item * n_nt;
-    if (item >= n_items[0]) return;
     const WorkItem it = items[item];
     if (it.expert < 0 || it.expert >= E || it.row_begin < 0) return;  // never index weights with a bad id
     const bf16_t *Bp = Wp + (size_t)it.expert * K * N;
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
         const int nrows = row_end - r0 < FFN_BM ? row_end - r0 : FFN_BM;
         f32x16_t acc[2][1];
         zero_acc<2, 1>(acc);
-        gemm_tile_bf16<2, 1>(A + (size_t)r0 * K, K, nrows, Bp, N, nt * FFN_BN, K, lds, acc);
+        gemm_tile_bf16<2, 1, FFN_BK>(A + (size_t)r0 * K, K, nrows, Bp, nt * FFN_BN, K, lds, acc);
         const int col = nt * FFN_BN + w * 32 + (lane & 31);
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
@@ -208,7 +209,8 @@ extern "C" int moe_pack_weights(const void *w, int E, int K, int N, int dtype, v
 {
     MOE_REQUIRE(E > 0 && K > 0 && N > 0, MOE_ERR_INVALID_ARG, "moe_pack_weights: E=%d K=%d N=%d out of range", E, K, N);
     MOE_REQUIRE(dtype == MOE_BF16, MOE_ERR_UNSUPPORTED, "moe_pack_weights: only MOE_BF16 weights are packed");
-    MOE_REQUIRE(K % 8 == 0, MOE_ERR_INVALID_ARG, "moe_pack_weights: K=%d is not a multiple of 8", K);
+    MOE_REQUIRE(K % 8 == 0 && N % 32 == 0, MOE_ERR_INVALID_ARG,
+                "moe_pack_weights: K=%d must be a multiple of 8 and N=%d of 32", K, N);
     MOE_REQUIRE(E <= 65535 && K / 8 <= 65535, MOE_ERR_UNSUPPORTED, "moe_pack_weights: E or K too large");
     MOE_REQUIRE(w && w_packed && w != w_packed, MOE_ERR_INVALID_ARG, "moe_pack_weights: null or aliased pointer");
     MOE_REQUIRE(aligned16(w_packed), MOE_ERR_INVALID_ARG, "moe_pack_weights: output misaligned");

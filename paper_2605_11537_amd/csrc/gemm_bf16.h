@@ -1,17 +1,25 @@
 // bf16 matrix-core tile product for gfx950, shared by the expert FFN, the router and the SRU
 // projections.
 //
-//   C[BM x BN] (fp32 accumulators) += A[rows, K] (row-major bf16, k contiguous)
-//                                   * B (packed bf16: element ((k/8)*N + n)*8 + k%8 = B[k][n])
+//   C[BM x BN] (fp32 accumulators) += A[rows, K] (row-major bf16, k contiguous) * B[K, N]
 //
-// One workgroup = 4 wavefronts.  Wavefront w owns NB column blocks of 32 (columns
-// n0 + (w*NB + nb)*32 ..) and all MB row blocks of 32, i.e. MB*NB v_mfma_f32_32x32x16_bf16
-// accumulators.  The B operand of that instruction wants, per lane, 8 consecutive k of one
-// column: in the packed layout that is one 16-byte load, 32 lanes reading 512 contiguous
-// bytes, so weights stream from HBM straight into registers exactly once per workgroup and
-// never pass through LDS.  The A rows (tokens) are shared by the four wavefronts and staged
-// through LDS in 64-wide k chunks, double buffered, with the next chunk's global loads (A and
-// B) issued before the current chunk's matrix instructions.
+// B is read from the packed image (see moe_pack_weights): columns are grouped in strips of
+// 32; inside a strip, for every group of 8 consecutive k, the 32 columns follow each other
+// with their 8 k-values contiguous (16 bytes).  uint4 index of (k/8 = g, column n):
+//     ((n/32) * (K/8) + g) * 32 + n%32
+// The B operand of v_mfma_f32_32x32x16_bf16 wants, per lane, 8 consecutive k of one column
+// (lanes 0-31: k 0-7, lanes 32-63: k 8-15 of the 16-deep step): in this image that is ONE
+// 16-byte load per lane, the 64 lanes of a wavefront reading 1 KB of consecutive memory, and
+// a wavefront walking down K reads one strip front to back.  Weights therefore stream from
+// HBM straight into registers exactly once per workgroup, in DRAM-page order, and never
+// pass through LDS.
+//
+// One workgroup = 4 wavefronts.  Wavefront w owns NB column strips (columns
+// n0 + (w*NB + nb)*32 ..) and all MB row blocks of 32 rows: MB*NB accumulators of 16 VGPRs.
+// The A rows (tokens) are shared by the four wavefronts and staged through LDS in BK-wide k
+// chunks, double buffered; the global loads of chunk i+1 (A and B) are issued before the
+// matrix instructions of chunk i, B registers ping-pong between two sets so nothing is
+// copied.
 #pragma once
 #include "common.h"
 
@@ -21,87 +29,97 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int GEMM_THREADS = 256;
-constexpr int GEMM_BK = 64;
-constexpr int GEMM_LDA = GEMM_BK + 8;  // LDS row stride in elements: 144 B keeps b128 reads conflict free
 
-template <int MB>
+template <int MB, int BK>
 constexpr int gemm_lds_elems()
 {
-    return 2 * MB * 32 * GEMM_LDA;
+    return 2 * MB * 32 * (BK + 8);   // row stride BK+8 elements keeps the b128 reads conflict free
 }
 
 // Row of accumulator register v (0..15) of a 32x32 block for this lane; its column is lane & 31.
 __device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
 // A: pointer to row 0 of the tile (already offset by the tile's first row); rows >= nrows read as 0.
-// Bp: packed matrix of this tile's expert; N = its column count; n0 = first column of the tile.
-template <int MB, int NB>
+// Bp: packed matrix (K x N) of this tile's expert; n0 = first column of the tile (multiple of 32).
+// K must be a multiple of BK.
+template <int MB, int NB, int BK>
 __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int lda, int nrows,
-                                               const bf16_t *__restrict__ Bp, int N, int n0, int K,
+                                               const bf16_t *__restrict__ Bp, int n0, int K,
                                                bf16_t *__restrict__ lds, f32x16_t (&acc)[MB][NB])
 {
+    constexpr int LDA = BK + 8;
+    constexpr int KS = BK / 16;                       // 16-deep MFMA steps per chunk
+    constexpr int PIECES = MB * 32 * (BK / 8);        // 16-byte pieces of one A chunk
+    constexpr int A_PER_THREAD = PIECES / GEMM_THREADS;
+    constexpr int ROW_STEP = GEMM_THREADS / (BK / 8);
+    static_assert(PIECES % GEMM_THREADS == 0, "A chunk must split evenly over the workgroup");
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int nk = K / GEMM_BK;
-    // A staging: chunk of MB*32 rows x 64 k = MB*256 16-byte pieces, MB per thread
-    uint4 a_reg[MB];
-    uint4 b_cur[4][NB], b_nxt[4][NB];
-    const int a_col = tid & 7;            // 16-byte piece within the 128-byte chunk row
-    const int a_row = tid >> 3;           // + i*32
-    const uint4 *b_base = reinterpret_cast<const uint4 *>(Bp) + (size_t)(lane >> 5) * N + n0 + w * NB * 32 + (lane & 31);
+    const int nk = K / BK;
+    const int KG = K >> 3;
+    uint4 a_reg[A_PER_THREAD];
+    uint4 b0[KS][NB], b1[KS][NB];
+    const int a_col = tid % (BK / 8);
+    const int a_row = tid / (BK / 8);
+    const uint4 *b_base = reinterpret_cast<const uint4 *>(Bp) + (size_t)((n0 >> 5) + w * NB) * KG * 32 + lane;
 
     auto load_a = [&](int kc) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            int r = a_row + i * 32;
-            a_reg[i] = r < nrows ? *reinterpret_cast<const uint4 *>(A + (size_t)r * lda + kc * GEMM_BK + a_col * 8)
+        for (int i = 0; i < A_PER_THREAD; ++i) {
+            int r = a_row + i * ROW_STEP;
+            a_reg[i] = r < nrows ? *reinterpret_cast<const uint4 *>(A + (size_t)r * lda + kc * BK + a_col * 8)
                                  : make_uint4(0, 0, 0, 0);
         }
     };
     auto store_a = [&](int buf) {
-        bf16_t *dst = lds + buf * (MB * 32 * GEMM_LDA);
+        bf16_t *dst = lds + buf * (MB * 32 * LDA);
 #pragma unroll
-        for (int i = 0; i < MB; ++i)
-            *reinterpret_cast<uint4 *>(dst + (a_row + i * 32) * GEMM_LDA + a_col * 8) = a_reg[i];
+        for (int i = 0; i < A_PER_THREAD; ++i)
+            *reinterpret_cast<uint4 *>(dst + (a_row + i * ROW_STEP) * LDA + a_col * 8) = a_reg[i];
     };
-    auto load_b = [&](int kc, uint4(&b)[4][NB]) {
+    auto load_b = [&](int kc, uint4(&b)[KS][NB]) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) b[ks][nb] = b_base[(size_t)(kc * 8 + ks * 2) * N + nb * 32];
+            for (int ks = 0; ks < KS; ++ks)
+                b[ks][nb] = b_base[((size_t)nb * KG + kc * (BK / 8) + ks * 2) * 32];
     };
-
-    load_a(0);
-    load_b(0, b_cur);
-    store_a(0);
-    __syncthreads();
-    for (int kc = 0; kc < nk; ++kc) {
-        const bool more = kc + 1 < nk;
-        if (more) {
-            load_a(kc + 1);
-            load_b(kc + 1, b_nxt);
-        }
-        const bf16_t *src = lds + (kc & 1) * (MB * 32 * GEMM_LDA) + (lane & 31) * GEMM_LDA + (lane >> 5) * 8;
+    auto compute = [&](int kc, const uint4(&b)[KS][NB]) {
+        const bf16_t *src = lds + (kc & 1) * (MB * 32 * LDA) + (lane & 31) * LDA + (lane >> 5) * 8;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
-                uint4 av = *reinterpret_cast<const uint4 *>(src + mb * 32 * GEMM_LDA + ks * 16);
+                uint4 av = *reinterpret_cast<const uint4 *>(src + mb * 32 * LDA + ks * 16);
                 bf16x8_t a = __builtin_bit_cast(bf16x8_t, av);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        a, __builtin_bit_cast(bf16x8_t, b_cur[ks][nb]), acc[mb][nb], 0, 0, 0);
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8_t, b[ks][nb]),
+                                                                          acc[mb][nb], 0, 0, 0);
             }
         }
+    };
+    // one pipeline stage: fetch chunk kc+1 into `nxt`, multiply chunk kc out of `cur`
+    auto stage = [&](int kc, const uint4(&cur)[KS][NB], uint4(&nxt)[KS][NB]) {
+        const bool more = kc + 1 < nk;
         if (more) {
-            store_a((kc + 1) & 1);
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) b_cur[ks][nb] = b_nxt[ks][nb];
+            load_a(kc + 1);
+            load_b(kc + 1, nxt);
         }
+        compute(kc, cur);
+        if (more) store_a((kc + 1) & 1);
         __syncthreads();
+    };
+
+    load_a(0);
+    load_b(0, b0);
+    store_a(0);
+    __syncthreads();
+    int kc = 0;
+    for (; kc + 1 < nk; kc += 2) {
+        stage(kc, b0, b1);
+        stage(kc + 1, b1, b0);
     }
+    if (kc < nk) stage(kc, b0, b1);
 }
 
 template <int MB, int NB>

@@ -11,7 +11,7 @@
 namespace moe {
 
 constexpr int PLAN_THREADS = 1024;
-constexpr int PLAN_PER_LANE = MOE_MAX_EXPERTS / WAVE;  // experts per lane of wavefront 0
+constexpr int PLAN_BATCH = 8;  // ids fetched per thread before any of them is counted
 
 __device__ __forceinline__ long long wave_sum_ll(long long v)
 {
@@ -20,6 +20,8 @@ __device__ __forceinline__ long long wave_sum_ll(long long v)
     return v;
 }
 
+// PLAN_PER_LANE = experts per lane of wavefront 0 (E <= 64 * PLAN_PER_LANE)
+template <int PLAN_PER_LANE>
 __global__ __launch_bounds__(PLAN_THREADS) void replica_plan_kernel(
     const int32_t *__restrict__ idx, int T, int E, int nbits, int R, int C, int policy,
     int32_t *__restrict__ plan_counts, int32_t *__restrict__ replicas, int32_t *__restrict__ slot_base,
@@ -35,17 +37,26 @@ __global__ __launch_bounds__(PLAN_THREADS) void replica_plan_kernel(
         rep[e] = 0;
     }
     __syncthreads();
-    for (int t0 = 0; t0 < T; t0 += PLAN_THREADS) {
-        int t = t0 + tid;
-        int e = t < T ? idx[t] : -1;
-        bool valid = e >= 0 && e < E;
-        unsigned long long mask = __ballot(valid);
-        for (int b = 0; b < nbits; ++b) {
-            bool bit = (e >> b) & 1;
-            unsigned long long bal = __ballot(bit);
-            mask &= bit ? bal : ~bal;
+    for (int t0 = 0; t0 < T; t0 += PLAN_THREADS * PLAN_BATCH) {
+        int eb[PLAN_BATCH];
+#pragma unroll
+        for (int u = 0; u < PLAN_BATCH; ++u) {
+            int t = t0 + u * PLAN_THREADS + tid;
+            eb[u] = t < T ? idx[t] : -1;
         }
-        if (valid && (mask & ((1ull << lane) - 1ull)) == 0) atomicAdd(&hist[e], __popcll(mask));
+#pragma unroll
+        for (int u = 0; u < PLAN_BATCH; ++u) {
+            int e = eb[u];
+            bool valid = e >= 0 && e < E;
+            unsigned long long mask = __ballot(valid);
+            if (mask == 0) continue;
+            for (int b = 0; b < nbits; ++b) {
+                bool bit = (e >> b) & 1;
+                unsigned long long bal = __ballot(bit);
+                mask &= bit ? bal : ~bal;
+            }
+            if (valid && (mask & ((1ull << lane) - 1ull)) == 0) atomicAdd(&hist[e], __popcll(mask));
+        }
     }
     __syncthreads();
 
@@ -197,9 +208,9 @@ extern "C" int replica_plan(const int32_t *idx, int T, int E, int budget, int sl
     MOE_REQUIRE((T == 0 || idx) && plan_counts && replicas, MOE_ERR_INVALID_ARG, "replica_plan: null pointer");
     int nbits = 0;
     while ((1 << nbits) < E) ++nbits;
-    hipLaunchKernelGGL(replica_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, (hipStream_t)stream, idx, T, E,
-                       nbits, budget, slot_capacity, policy, plan_counts, replicas, slot_base, slot_expert,
-                       n_slots);
+    auto kern = E <= 128 ? replica_plan_kernel<2> : E <= 256 ? replica_plan_kernel<4> : replica_plan_kernel<16>;
+    hipLaunchKernelGGL(kern, dim3(1), dim3(PLAN_THREADS), 0, (hipStream_t)stream, idx, T, E, nbits, budget,
+                       slot_capacity, policy, plan_counts, replicas, slot_base, slot_expert, n_slots);
     MOE_CHECK_LAUNCH("replica_plan");
     return MOE_OK;
 }

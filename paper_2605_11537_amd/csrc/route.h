@@ -5,8 +5,8 @@
 
 namespace moe {
 size_t route_ws_bytes(int d, int E, int dtype);
-int route_launch(const void *x, const void *w_router, const float *b_router, int T, int d, int E, int dtype,
-                 int32_t *idx, float *prob, float *logits_opt, void *ws, hipStream_t st, const char *who);
-// in [K][N] bf16 row-major -> packed image, element ((k/8)*N + n)*8 + k%8
+int route_launch(const void *x, const void *w_router, int w_layout, const float *b_router, int T, int d, int E,
+                 int dtype, int32_t *idx, float *prob, float *logits_opt, void *ws, hipStream_t st, const char *who);
+// in [K][N] bf16 row-major -> packed image (N a multiple of 32), 16-byte piece ((n/32)*(K/8) + k/8)*32 + n%32
 int pack_matrix_launch(const void *in, int K, int N, void *out, hipStream_t st, const char *who);
 }  // namespace moe

@@ -3,7 +3,7 @@
 //
 //   bf16, E a multiple of 128 (<= 256): matrix-core kernel.  The [d,E] router matrix is first
 //     re-laid into the packed k-major image the MFMA B operand wants (a few hundred KB, one
-//     small kernel into the workspace), then each workgroup multiplies a 64-token tile with
+//     small kernel into the workspace), then each workgroup multiplies a 32-token tile with
 //     all E columns and reduces each row (max, first arg-max, sum of exponentials) in LDS.
 //   anything else (fp32 tensors, small or odd E): one wavefront per token, lanes over
 //     experts, binary32 FMA in ascending k.
@@ -12,7 +12,8 @@
 
 namespace moe {
 
-constexpr int RT_BM = 64;
+constexpr int RT_BM = 32;    // tokens per workgroup: small tiles, many workgroups
+constexpr int RT_BK = 128;
 
 __device__ __forceinline__ void argmax_merge(float &v, int &i, float ov, int oi)
 {
@@ -22,7 +23,7 @@ __device__ __forceinline__ void argmax_merge(float &v, int &i, float ov, int oi)
     }
 }
 
-// in [K][N] bf16 row-major -> packed image ((k/8)*N + n)*8 + k%8
+// in [K][N] bf16 row-major -> packed image, 16-byte piece ((n/32)*(K/8) + k/8)*32 + n%32
 __global__ __launch_bounds__(256) void pack_matrix_kernel(const bf16_t *__restrict__ in, int K, int N,
                                                           uint4 *__restrict__ out)
 {
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(256) void pack_matrix_kernel(const bf16_t *__restri
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         v[j] = (uint32_t)src[(size_t)(2 * j) * N] | ((uint32_t)src[(size_t)(2 * j + 1) * N] << 16);
-    out[i] = make_uint4(v[0], v[1], v[2], v[3]);
+    out[((size_t)(n >> 5) * (K / 8) + kg) * 32 + (n & 31)] = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
 template <int NB>
@@ -46,21 +47,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *
 {
     constexpr int E = NB * 128;
     constexpr int LDL = E + 4;
-    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2>()];
+    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<1, RT_BK>()];
     __shared__ float tile[32 * LDL];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int row0 = blockIdx.x * RT_BM;
     const int nrows = T - row0 < RT_BM ? T - row0 : RT_BM;
-    f32x16_t acc[2][NB];
-    zero_acc<2, NB>(acc);
-    gemm_tile_bf16<2, NB>(x + (size_t)row0 * d, d, nrows, wr_packed, E, 0, d, lds, acc);
+    f32x16_t acc[1][NB];
+    zero_acc<1, NB>(acc);
+    gemm_tile_bf16<1, NB, RT_BK>(x + (size_t)row0 * d, d, nrows, wr_packed, 0, d, lds, acc);
 
     float b[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) b[nb] = bias ? bias[(w * NB + nb) * 32 + (lane & 31)] : 0.f;
 
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
+    constexpr int mb = 0;
+    {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(256) void route_generic_kernel(const void *__restri
 
 static inline bool route_uses_mfma(int d, int E, int dtype)
 {
-    return dtype == MOE_BF16 && (E == 128 || E == 256) && d % GEMM_BK == 0;
+    return dtype == MOE_BF16 && (E == 128 || E == 256) && d % RT_BK == 0;
 }
 
 int pack_matrix_launch(const void *in, int K, int N, void *out, hipStream_t st, const char *who)
@@ -165,19 +166,23 @@ int pack_matrix_launch(const void *in, int K, int N, void *out, hipStream_t st, 
 }
 
 // shared with sru_predict (its head is the same product + argmax)
-int route_launch(const void *x, const void *w_router, const float *b_router, int T, int d, int E, int dtype,
-                 int32_t *idx, float *prob, float *logits_opt, void *ws, hipStream_t st, const char *who)
+int route_launch(const void *x, const void *w_router, int w_layout, const float *b_router, int T, int d, int E,
+                 int dtype, int32_t *idx, float *prob, float *logits_opt, void *ws, hipStream_t st, const char *who)
 {
     if (route_uses_mfma(d, E, dtype)) {
-        int rc = pack_matrix_launch(w_router, d, E, ws, st, who);
-        if (rc != MOE_OK) return rc;
+        const void *wp = w_router;
+        if (w_layout == MOE_LAYOUT_PLAIN) {
+            int rc = pack_matrix_launch(w_router, d, E, ws, st, who);
+            if (rc != MOE_OK) return rc;
+            wp = ws;
+        }
         int grid = ceil_div(T, RT_BM);
         if (E == 128)
             hipLaunchKernelGGL(route_mfma_kernel<1>, dim3(grid), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x,
-                               (const bf16_t *)ws, b_router, T, d, idx, prob, logits_opt);
+                               (const bf16_t *)wp, b_router, T, d, idx, prob, logits_opt);
         else
             hipLaunchKernelGGL(route_mfma_kernel<2>, dim3(grid), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x,
-                               (const bf16_t *)ws, b_router, T, d, idx, prob, logits_opt);
+                               (const bf16_t *)wp, b_router, T, d, idx, prob, logits_opt);
     } else if (dtype == MOE_BF16) {
         hipLaunchKernelGGL(route_generic_kernel<true>, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, w_router, b_router, T,
                            d, E, idx, prob, logits_opt);
@@ -205,20 +210,24 @@ extern "C" size_t moe_route_workspace_bytes(int T, int d, int E, int dtype)
     return route_ws_bytes(d, E, dtype);
 }
 
-extern "C" int moe_route(const void *x, const void *w_router, const float *b_router, int T, int d, int E, int dtype,
-                         int32_t *expert_idx, float *expert_prob, float *logits_opt, void *ws, size_t ws_bytes,
-                         void *stream)
+extern "C" int moe_route(const void *x, const void *w_router, int w_layout, const float *b_router, int T, int d,
+                         int E, int dtype, int32_t *expert_idx, float *expert_prob, float *logits_opt, void *ws,
+                         size_t ws_bytes, void *stream)
 {
+    MOE_REQUIRE(w_layout == MOE_LAYOUT_PLAIN || w_layout == MOE_LAYOUT_PACKED, MOE_ERR_INVALID_ARG,
+                "moe_route: unknown weight layout %d", w_layout);
     MOE_REQUIRE(T >= 0 && d > 0 && E > 0, MOE_ERR_INVALID_ARG, "moe_route: T=%d d=%d E=%d out of range", T, d, E);
     MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_INVALID_ARG, "moe_route: unknown dtype %d", dtype);
     MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_route: E=%d exceeds %d", E, MOE_MAX_EXPERTS);
     MOE_REQUIRE(d % 8 == 0, MOE_ERR_INVALID_ARG, "moe_route: d=%d is not a multiple of 8", d);
+    MOE_REQUIRE(w_layout == MOE_LAYOUT_PLAIN || route_uses_mfma(d, E, dtype), MOE_ERR_UNSUPPORTED,
+                "moe_route: a packed router matrix needs bf16, E = 128 or 256 and d a multiple of %d", RT_BK);
     if (T == 0) return MOE_OK;
     MOE_REQUIRE(x && w_router && expert_idx && expert_prob, MOE_ERR_INVALID_ARG, "moe_route: null pointer");
     MOE_REQUIRE(aligned16(x) && aligned16(w_router), MOE_ERR_INVALID_ARG, "moe_route: tensor misaligned");
     size_t need = route_ws_bytes(d, E, dtype);
     MOE_REQUIRE(ws && aligned16(ws) && ws_bytes >= need, MOE_ERR_WORKSPACE,
                 "moe_route: workspace of %zu bytes needed, %zu given", need, ws_bytes);
-    return route_launch(x, w_router, b_router, T, d, E, dtype, expert_idx, expert_prob, logits_opt, ws,
+    return route_launch(x, w_router, w_layout, b_router, T, d, E, dtype, expert_idx, expert_prob, logits_opt, ws,
                         (hipStream_t)stream, "moe_route");
 }

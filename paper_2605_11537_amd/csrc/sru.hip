@@ -21,7 +21,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void sru_proj_kernel(const bf16_t *__
                                                                 const bf16_t *__restrict__ Wp, int T, int K, int N,
                                                                 float *__restrict__ U)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2>()];
+    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2, 64>()];
     const int n_nt = N / 128;
     const int mt = blockIdx.x / n_nt, nt = blockIdx.x - mt * n_nt;
     const int row0 = mt * 64;
@@ -29,7 +29,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void sru_proj_kernel(const bf16_t *__
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     f32x16_t acc[2][1];
     zero_acc<2, 1>(acc);
-    gemm_tile_bf16<2, 1>(X + (size_t)row0 * K, K, nrows, Wp, N, nt * 128, K, lds, acc);
+    gemm_tile_bf16<2, 1, 64>(X + (size_t)row0 * K, K, nrows, Wp, nt * 128, K, lds, acc);
     const int col = nt * 128 + w * 32 + (lane & 31);
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -176,6 +176,6 @@ extern "C" int sru_predict(const void *emb, const sru_weights *w, int B, int L, 
         cur = out;
         nin = n_h;
     }
-    return route_launch(cur, w->w_head, w->b_head, T, n_h, w->n_out, MOE_BF16, pred_idx, (float *)(base + lay.prob),
+    return route_launch(cur, w->w_head, MOE_LAYOUT_PLAIN, w->b_head, T, n_h, w->n_out, MOE_BF16, pred_idx, (float *)(base + lay.prob),
                         logits_opt, base + lay.rws, st, "sru_predict/head");
 }

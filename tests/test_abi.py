@@ -46,13 +46,16 @@ def test_invalid_arguments_are_rejected_on_the_host():
     buf = (C.c_char * 4096)()
     p = C.cast(buf, C.c_void_p)
     INV, UNS, WS = -1, -2, -3
+    q = C.cast(C.addressof(buf) + 1024, C.c_void_p)
     # moe_route
-    assert L.moe_route(p, p, None, -1, 64, 8, 0, p, p, None, p, 4096, None) == INV
-    assert L.moe_route(p, p, None, 4, 60, 8, 0, p, p, None, p, 4096, None) == INV       # d % 8
-    assert L.moe_route(None, p, None, 4, 64, 8, 0, p, p, None, p, 4096, None) == INV
-    assert L.moe_route(p, p, None, 4, 64, 8, 7, p, p, None, p, 4096, None) == INV       # dtype
-    assert L.moe_route(p, p, None, 4, 64, 2048, 0, p, p, None, p, 4096, None) == UNS
-    assert L.moe_route(p, p, None, 4, 768, 128, 1, p, p, None, p, 16, None) == WS
+    assert L.moe_route(p, p, 0, None, -1, 64, 8, 0, p, p, None, p, 4096, None) == INV
+    assert L.moe_route(p, p, 0, None, 4, 60, 8, 0, p, p, None, p, 4096, None) == INV       # d % 8
+    assert L.moe_route(None, p, 0, None, 4, 64, 8, 0, p, p, None, p, 4096, None) == INV
+    assert L.moe_route(p, p, 0, None, 4, 64, 8, 7, p, p, None, p, 4096, None) == INV       # dtype
+    assert L.moe_route(p, p, 2, None, 4, 64, 8, 0, p, p, None, p, 4096, None) == INV       # layout
+    assert L.moe_route(p, p, 1, None, 4, 64, 8, 0, p, p, None, p, 4096, None) == UNS       # packed fp32
+    assert L.moe_route(p, p, 0, None, 4, 64, 2048, 0, p, p, None, p, 4096, None) == UNS
+    assert L.moe_route(p, p, 0, None, 4, 768, 128, 1, p, p, None, p, 16, None) == WS
     assert b"workspace" in L.moe_last_error()
     # replica_plan
     assert L.replica_plan(p, 4, 8, -1, 1, 0, p, p, p, p, p, None) == INV
@@ -65,7 +68,9 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.moe_dispatch(p, p, None, 4, 64, 8, 1, 4, 0, p, p, p, p, p, p, p, p, 4096, None) == INV  # max_slots < E
     assert L.moe_dispatch(p, p, None, 4, 64, 8, 1, 8, 0, p, p, p, p, p, p, p, None, 0, None) == WS
     # moe_pack_weights / moe_expert_ffn
-    assert L.moe_pack_weights(p, 2, 12, 16, 1, p, None) == INV                       # K % 8 / aliasing
+    assert L.moe_pack_weights(p, 2, 12, 32, 1, q, None) == INV                       # K % 8
+    assert L.moe_pack_weights(p, 2, 16, 16, 1, q, None) == INV                       # N % 32
+    assert L.moe_pack_weights(p, 2, 16, 32, 1, p, None) == INV                       # aliasing
     assert L.moe_pack_weights(p, 2, 16, 16, 0, p, None) == UNS
     assert L.moe_expert_ffn(p, p, p, 0, p, p, p, 4, 8, 8, 768, 3072, 1, 0, p, p, 1 << 30, None) == UNS  # plain bf16
     assert L.moe_expert_ffn(p, p, p, 1, p, p, p, 4, 8, 8, 100, 3072, 1, 0, p, p, 1 << 30, None) == UNS  # d % 128
@@ -73,7 +78,6 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.moe_expert_ffn(p, p, p, 0, p, p, p, 4, 8, 8, 64, 256, 0, 0, p, p, 16, None) == WS
     # moe_combine
     assert L.moe_combine(p, p, p, p, 4, 64, 0, 2, p, None) == INV                     # residual flag
-    q = C.cast(C.addressof(buf) + 1024, C.c_void_p)
     assert L.moe_combine(p, q, p, p, 4, 64, 0, 0, q, None) == INV                     # out aliases x
     # sru_predict
     w = moe.binding.SruWeightsC(2, 768, 256, 128, None, None, None, None, None)
