@@ -99,6 +99,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a reference dispatch of known size for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--modes", default="on,off_same_plan,off_budget0",
                     help="replication modes to time besides 'on' (comma list)")
     a = ap.parse_args()
@@ -181,6 +184,14 @@ def main():
             modes[name] = round(T / (ms * 1e-3), 1)
             extra_ms[name] = round(ms, 5)
     kept0 = int(layer0.disp_out["kept"].sum().item()) if "off_budget0" in modes else None
+
+    if a.pmc_calibration_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = None
     if not a.no_cpu_baseline:

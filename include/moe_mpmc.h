@@ -172,9 +172,15 @@ int moe_pack_weights(const void *w, int E, int K, int N, int dtype, void *w_pack
  * the one physical expert).  Both produce the same y_perm.  max_rows bounds the rows
  * (normally T), max_slots the slot tables, E the expert count of W1/W2 (slots naming an
  * expert outside [0,E) are skipped).  Rows outside all slots are not written.
+ * row_index (may be NULL): fused gather.  When given, row r of the permuted row space is read
+ * from x_perm[row_index[r]] -- pass the token matrix x as x_perm and moe_dispatch's perm as
+ * row_index, and call moe_dispatch with x = x_perm = NULL: the permuted copy of the tokens is
+ * then never written to HBM.  x_perm must hold max_rows rows; an index outside [0, max_rows)
+ * reads as a zero row.  y_perm stays in permuted row order either way.
  */
 size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, int d, int F, int dtype);
-int moe_expert_ffn(const void *x_perm, const void *w1, const void *w2, int weight_layout,
+int moe_expert_ffn(const void *x_perm, const int32_t *row_index, const void *w1, const void *w2,
+                   int weight_layout,
                    const int32_t *slot_offset, const int32_t *slot_expert, const int32_t *n_slots,
                    int max_rows, int max_slots, int E, int d, int F, int dtype, int schedule,
                    void *y_perm, void *ws, size_t ws_bytes, void *stream);

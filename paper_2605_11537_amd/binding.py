@@ -68,7 +68,7 @@ def lib():
         _lib.moe_packed_weights_bytes.argtypes = [I, I, I, I]
         _lib.moe_pack_weights.argtypes = [P, I, I, I, I, P, P]
         _lib.moe_expert_ffn_workspace_bytes.argtypes = [I, I, I, I, I]
-        _lib.moe_expert_ffn.argtypes = [P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P]
+        _lib.moe_expert_ffn.argtypes = [P, P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P]
         _lib.moe_expert_ffn_set_timing_events.argtypes = [P, P, P]
         _lib.moe_combine.argtypes = [P, P, P, P, I, I, I, I, P, P]
     return _lib
@@ -173,17 +173,21 @@ def replica_plan(idx, E, budget, slot_capacity, policy=0, out=None):
     return o
 
 
-def moe_dispatch(x, expert_idx, replicas, E, slot_capacity, max_slots, out=None, ws=None):
-    """-> dict(counts, kept, expert_offset, slot_offset, perm, inv, x_perm)."""
-    T, d = x.shape
-    dev = x.device
+def moe_dispatch(x, expert_idx, replicas, E, slot_capacity, max_slots, out=None, ws=None, shape=None,
+                 dtype=None):
+    """-> dict(counts, kept, expert_offset, slot_offset, perm, inv, x_perm).  With x=None (give
+    ``shape=(T, d)`` and ``dtype``) only the index tables are built and no rows are copied."""
+    T, d = x.shape if x is not None else shape
+    dev = expert_idx.device
+    dt = _dt(x) if x is not None else (MOE_BF16 if dtype == torch.bfloat16 else MOE_F32)
     o = out if out is not None else dict(counts=_i32(E, dev), kept=_i32(E, dev), expert_offset=_i32(E + 1, dev),
                                          slot_offset=_i32(max_slots + 1, dev), perm=_i32(T, dev),
-                                         inv=_i32(T, dev), x_perm=torch.empty_like(x))
+                                         inv=_i32(T, dev), x_perm=torch.empty_like(x) if x is not None else None)
     ws = ws if ws is not None else _ws(lib().moe_dispatch_workspace_bytes(T, E), dev)
-    _check(lib().moe_dispatch(_ptr(x), _ptr(expert_idx), _ptr(replicas), T, d, E, slot_capacity, max_slots, _dt(x),
+    xp = o["x_perm"] if x is not None else None
+    _check(lib().moe_dispatch(_ptr(x), _ptr(expert_idx), _ptr(replicas), T, d, E, slot_capacity, max_slots, dt,
                               _ptr(o["counts"]), _ptr(o["kept"]), _ptr(o["expert_offset"]), _ptr(o["slot_offset"]),
-                              _ptr(o["perm"]), _ptr(o["inv"]), _ptr(o["x_perm"]), _ptr(ws), ws.numel(), _stream()))
+                              _ptr(o["perm"]), _ptr(o["inv"]), _ptr(xp), _ptr(ws), ws.numel(), _stream()))
     return o
 
 
@@ -196,8 +200,9 @@ def moe_pack_weights(w, out=None):
 
 
 def moe_expert_ffn(x_perm, w1, w2, slot_offset, slot_expert, n_slots, E, F, max_slots=None,
-                   schedule=SCHEDULE_SLOTS, weight_layout=None, out=None, ws=None):
-    """-> y_perm [max_rows, d].  bf16 weights must already be packed (``moe_pack_weights``)."""
+                   schedule=SCHEDULE_SLOTS, weight_layout=None, out=None, ws=None, row_index=None):
+    """-> y_perm [max_rows, d].  bf16 weights must already be packed (``moe_pack_weights``).
+    With row_index (moe_dispatch's perm), x_perm is the unpermuted token matrix (fused gather)."""
     max_rows, d = x_perm.shape
     dev = x_perm.device
     dt = _dt(x_perm)
@@ -207,7 +212,7 @@ def moe_expert_ffn(x_perm, w1, w2, slot_offset, slot_expert, n_slots, E, F, max_
         max_slots = slot_expert.shape[0]
     y = out if out is not None else torch.empty_like(x_perm)
     ws = ws if ws is not None else _ws(lib().moe_expert_ffn_workspace_bytes(max_rows, max_slots, d, F, dt), dev)
-    _check(lib().moe_expert_ffn(_ptr(x_perm), _ptr(w1), _ptr(w2), weight_layout, _ptr(slot_offset),
+    _check(lib().moe_expert_ffn(_ptr(x_perm), _ptr(row_index), _ptr(w1), _ptr(w2), weight_layout, _ptr(slot_offset),
                                 _ptr(slot_expert), _ptr(n_slots), max_rows, max_slots, E, d, F, dt, schedule,
                                 _ptr(y), _ptr(ws), ws.numel(), _stream()))
     return y
@@ -253,15 +258,16 @@ class MoeLayer:
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
 
     def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
-                out=None, budget=None, router_layout=LAYOUT_PLAIN):
+                out=None, budget=None, router_layout=LAYOUT_PLAIN, fuse_gather=True):
         idx, prob, _ = moe_route(x, w_router, b_router, out=self.route_out, ws=self.route_ws,
                                  w_layout=router_layout)
         R = self.R if budget is None else budget
         if R != self.R:
             raise ValueError("budget is fixed by the preallocated slot tables")
         pl = replica_plan(idx if plan_ids is None else plan_ids, self.E, R, self.C, self.policy, out=self.plan_out)
-        dp = moe_dispatch(x, idx, pl["replicas"], self.E, self.C, self.max_slots, out=self.disp_out,
-                          ws=self.disp_ws)
-        y = moe_expert_ffn(dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"], pl["n_slots"], self.E,
-                           self.F, max_slots=self.max_slots, schedule=schedule, out=self.y_perm, ws=self.ffn_ws)
+        dp = moe_dispatch(None if fuse_gather else x, idx, pl["replicas"], self.E, self.C, self.max_slots,
+                          out=self.disp_out, ws=self.disp_ws, shape=(self.T, self.d), dtype=x.dtype)
+        y = moe_expert_ffn(x if fuse_gather else dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"],
+                           pl["n_slots"], self.E, self.F, max_slots=self.max_slots, schedule=schedule,
+                           out=self.y_perm, ws=self.ffn_ws, row_index=dp["perm"] if fuse_gather else None)
         return moe_combine(y, x, dp["inv"], prob, residual, out=self.out if out is None else out)

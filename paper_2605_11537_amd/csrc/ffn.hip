@@ -93,8 +93,9 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
 // ------------------------------------------------------------------ bf16 grouped GEMM
 template <bool RELU>
 __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
-    const bf16_t *__restrict__ A, const bf16_t *__restrict__ Wp, int K, int N, int E,
-    const WorkItem *__restrict__ items, const int32_t *__restrict__ n_items, int max_rows, bf16_t *__restrict__ C)
+    const bf16_t *__restrict__ A, const int32_t *__restrict__ row_index, int n_src_rows,
+    const bf16_t *__restrict__ Wp, int K, int N, int E, const WorkItem *__restrict__ items,
+    const int32_t *__restrict__ n_items, int max_rows, bf16_t *__restrict__ C)
 {
     __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2, FFN_BK>()];
     const int n_nt = N / FFN_BN;
@@ -110,7 +111,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
         const int nrows = row_end - r0 < FFN_BM ? row_end - r0 : FFN_BM;
         f32x16_t acc[2][1];
         zero_acc<2, 1>(acc);
-        gemm_tile_bf16<2, 1, FFN_BK>(A + (size_t)r0 * K, K, nrows, Bp, nt * FFN_BN, K, lds, acc);
+        if (row_index)
+            gemm_tile_bf16<2, 1, FFN_BK>(A, K, nrows, Bp, nt * FFN_BN, K, lds, acc, row_index + r0, n_src_rows);
+        else
+            gemm_tile_bf16<2, 1, FFN_BK>(A + (size_t)r0 * K, K, nrows, Bp, nt * FFN_BN, K, lds, acc);
         const int col = nt * FFN_BN + w * 32 + (lane & 31);
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
@@ -130,7 +134,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
 // 64x64 tile, 256 threads, 4x4 outputs per thread, k ascending.
 template <bool RELU>
 __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W,
-                                                           int K, int N, int E, const WorkItem *__restrict__ items,
+                                                           const int32_t *__restrict__ row_index, int K, int N, int E,
+                                                           const WorkItem *__restrict__ items,
                                                            const int32_t *__restrict__ n_items, int max_rows,
                                                            float *__restrict__ C)
 {
@@ -151,7 +156,10 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restri
             {   // A chunk 64 rows x 16 k: thread loads 4 consecutive k of one row
                 int r = threadIdx.x >> 2, kq = (threadIdx.x & 3) * 4;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (r < nrows) v = *reinterpret_cast<const float4 *>(A + (size_t)(r0 + r) * K + k0 + kq);
+                if (r < nrows) {
+                    int src = row_index ? row_index[r0 + r] : r0 + r;
+                    if (src >= 0 && src < max_rows) v = *reinterpret_cast<const float4 *>(A + (size_t)src * K + k0 + kq);
+                }
                 As[kq + 0][r] = v.x;
                 As[kq + 1][r] = v.y;
                 As[kq + 2][r] = v.z;
@@ -237,7 +245,8 @@ extern "C" size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, in
     return h + items + 256;
 }
 
-extern "C" int moe_expert_ffn(const void *x_perm, const void *w1, const void *w2, int weight_layout,
+extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, const void *w1, const void *w2,
+                              int weight_layout,
                               const int32_t *slot_offset, const int32_t *slot_expert, const int32_t *n_slots,
                               int max_rows, int max_slots, int E, int d, int F, int dtype, int schedule,
                               void *y_perm, void *ws, size_t ws_bytes, void *stream)
@@ -293,20 +302,22 @@ extern "C" int moe_expert_ffn(const void *x_perm, const void *w1, const void *w2
         int g1 = (int)align_up((size_t)grid_items * (F / FFN_BN), 8);
         int g2 = (int)align_up((size_t)grid_items * (d / FFN_BN), 8);
         hipLaunchKernelGGL(ffn_gemm_bf16_kernel<true>, dim3(g1), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x_perm,
-                           (const bf16_t *)w1, d, F, E, items, n_items, max_rows, (bf16_t *)h);
+                           row_index, max_rows, (const bf16_t *)w1, d, F, E, items, n_items, max_rows, (bf16_t *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
         if (ev[1]) (void)hipEventRecord(ev[1], st);
         hipLaunchKernelGGL(ffn_gemm_bf16_kernel<false>, dim3(g2), dim3(GEMM_THREADS), 0, st, (const bf16_t *)h,
-                           (const bf16_t *)w2, F, d, E, items, n_items, max_rows, (bf16_t *)y_perm);
+                           (const int32_t *)nullptr, max_rows, (const bf16_t *)w2, F, d, E, items, n_items, max_rows,
+                           (bf16_t *)y_perm);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm2");
     } else {
         int g1 = grid_items * (F / 64), g2 = grid_items * (d / 64);
         hipLaunchKernelGGL(ffn_gemm_f32_kernel<true>, dim3(g1), dim3(256), 0, st, (const float *)x_perm,
-                           (const float *)w1, d, F, E, items, n_items, max_rows, (float *)h);
+                           (const float *)w1, row_index, d, F, E, items, n_items, max_rows, (float *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
         if (ev[1]) (void)hipEventRecord(ev[1], st);
         hipLaunchKernelGGL(ffn_gemm_f32_kernel<false>, dim3(g2), dim3(256), 0, st, (const float *)h,
-                           (const float *)w2, F, d, E, items, n_items, max_rows, (float *)y_perm);
+                           (const float *)w2, (const int32_t *)nullptr, F, d, E, items, n_items, max_rows,
+                           (float *)y_perm);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm2");
     }
     if (ev[2]) (void)hipEventRecord(ev[2], st);

@@ -40,12 +40,15 @@ constexpr int gemm_lds_elems()
 __device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
 // A: pointer to row 0 of the tile (already offset by the tile's first row); rows >= nrows read as 0.
+// row_idx (optional, already offset to the tile's first row): tile row r is read from
+//   A + row_idx[r]*lda instead of A + r*lda (fused gather of token rows).
 // Bp: packed matrix (K x N) of this tile's expert; n0 = first column of the tile (multiple of 32).
 // K must be a multiple of BK.
 template <int MB, int NB, int BK>
 __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int lda, int nrows,
                                                const bf16_t *__restrict__ Bp, int n0, int K,
-                                               bf16_t *__restrict__ lds, f32x16_t (&acc)[MB][NB])
+                                               bf16_t *__restrict__ lds, f32x16_t (&acc)[MB][NB],
+                                               const int32_t *__restrict__ row_idx = nullptr, int n_src_rows = 0)
 {
     constexpr int LDA = BK + 8;
     constexpr int KS = BK / 16;                       // 16-deep MFMA steps per chunk
@@ -62,13 +65,23 @@ __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int
     const int a_row = tid / (BK / 8);
     const uint4 *b_base = reinterpret_cast<const uint4 *>(Bp) + (size_t)((n0 >> 5) + w * NB) * KG * 32 + lane;
 
+    const bf16_t *a_src[A_PER_THREAD];   // this thread's rows stay the same for every k chunk
+    bool a_ok[A_PER_THREAD];             // rows past the tile, or an index outside the source, read as 0
+#pragma unroll
+    for (int i = 0; i < A_PER_THREAD; ++i) {
+        int r = a_row + i * ROW_STEP;
+        a_ok[i] = r < nrows;
+        int src_row = r;
+        if (row_idx && a_ok[i]) {
+            src_row = row_idx[r];
+            a_ok[i] = src_row >= 0 && src_row < n_src_rows;
+        }
+        a_src[i] = A + (size_t)(a_ok[i] ? src_row : 0) * lda + a_col * 8;
+    }
     auto load_a = [&](int kc) {
 #pragma unroll
-        for (int i = 0; i < A_PER_THREAD; ++i) {
-            int r = a_row + i * ROW_STEP;
-            a_reg[i] = r < nrows ? *reinterpret_cast<const uint4 *>(A + (size_t)r * lda + kc * BK + a_col * 8)
-                                 : make_uint4(0, 0, 0, 0);
-        }
+        for (int i = 0; i < A_PER_THREAD; ++i)
+            a_reg[i] = a_ok[i] ? *reinterpret_cast<const uint4 *>(a_src[i] + kc * BK) : make_uint4(0, 0, 0, 0);
     };
     auto store_a = [&](int buf) {
         bf16_t *dst = lds + buf * (MB * 32 * LDA);

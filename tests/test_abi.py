@@ -72,10 +72,10 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.moe_pack_weights(p, 2, 16, 16, 1, q, None) == INV                       # N % 32
     assert L.moe_pack_weights(p, 2, 16, 32, 1, p, None) == INV                       # aliasing
     assert L.moe_pack_weights(p, 2, 16, 16, 0, p, None) == UNS
-    assert L.moe_expert_ffn(p, p, p, 0, p, p, p, 4, 8, 8, 768, 3072, 1, 0, p, p, 1 << 30, None) == UNS  # plain bf16
-    assert L.moe_expert_ffn(p, p, p, 1, p, p, p, 4, 8, 8, 100, 3072, 1, 0, p, p, 1 << 30, None) == UNS  # d % 128
-    assert L.moe_expert_ffn(p, p, p, 0, p, p, p, 4, 8, 8, 64, 256, 0, 5, p, p, 1 << 30, None) == INV   # schedule
-    assert L.moe_expert_ffn(p, p, p, 0, p, p, p, 4, 8, 8, 64, 256, 0, 0, p, p, 16, None) == WS
+    assert L.moe_expert_ffn(p, None, p, p, 0, p, p, p, 4, 8, 8, 768, 3072, 1, 0, p, p, 1 << 30, None) == UNS  # plain bf16
+    assert L.moe_expert_ffn(p, None, p, p, 1, p, p, p, 4, 8, 8, 100, 3072, 1, 0, p, p, 1 << 30, None) == UNS  # d % 128
+    assert L.moe_expert_ffn(p, None, p, p, 0, p, p, p, 4, 8, 8, 64, 256, 0, 5, p, p, 1 << 30, None) == INV   # schedule
+    assert L.moe_expert_ffn(p, None, p, p, 0, p, p, p, 4, 8, 8, 64, 256, 0, 0, p, p, 16, None) == WS
     # moe_combine
     assert L.moe_combine(p, p, p, p, 4, 64, 0, 2, p, None) == INV                     # residual flag
     assert L.moe_combine(p, q, p, p, 4, 64, 0, 0, q, None) == INV                     # out aliases x

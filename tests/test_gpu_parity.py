@@ -211,7 +211,7 @@ def test_ffn_bf16_ragged_slots(schedule):
 
 
 # --------------------------------------------------------------------------- whole layer
-def _run_layer_gpu(c, C, R, schedule=0, residual=0, plan_ids=None, packed=None):
+def _run_layer_gpu(c, C, R, schedule=0, residual=0, plan_ids=None, packed=None, fuse_gather=True):
     dt = torch.bfloat16 if c["dtype"] == synth.BF16 else torch.float32
     layer = moe.MoeLayer(c["T"], c["d"], c["F"], c["E"], R, C, dt)
     x, wr, b = to_dev(c["x"]), to_dev(c["w_router"]), to_dev(c["b_router"])
@@ -221,7 +221,8 @@ def _run_layer_gpu(c, C, R, schedule=0, residual=0, plan_ids=None, packed=None):
             w1, w2 = moe.moe_pack_weights(w1), moe.moe_pack_weights(w2)
     else:
         w1, w2 = packed
-    out = layer.forward(x, wr, b, w1, w2, plan_ids=plan_ids, schedule=schedule, residual=residual)
+    out = layer.forward(x, wr, b, w1, w2, plan_ids=plan_ids, schedule=schedule, residual=residual,
+                        fuse_gather=fuse_gather)
     _sync()
     return layer, out, (w1, w2)
 
@@ -262,7 +263,7 @@ def _compare_layer(c, C, R, layer, out, residual=0, rows=None, plan_ids_host=Non
 @pytest.mark.parametrize("residual", [0, 1])
 def test_layer_config1(schedule, residual):
     c = synth.config_inputs(1)
-    layer, out, _ = _run_layer_gpu(c, c["C"], c["R"], schedule, residual)
+    layer, out, _ = _run_layer_gpu(c, c["C"], c["R"], schedule, residual, fuse_gather=bool(schedule))
     flips, K = _compare_layer(c, c["C"], c["R"], layer, out, residual)
     assert flips == 0 and K == c["T"]
 
@@ -270,8 +271,15 @@ def test_layer_config1(schedule, residual):
 @pytest.mark.parametrize("T,E,C,R", [(700, 8, 60, 3), (1500, 16, 50, 0), (2000, 128, 10, 16)])
 def test_layer_bf16_small_with_drops(T, E, C, R):
     c = synth.moe_layer_inputs(T, 128, 256, E, synth.BF16, 1.1, 70 + T)
-    layer, out, _ = _run_layer_gpu(c, C, R)
+    layer, out, packed = _run_layer_gpu(c, C, R)
+    fused = out.clone()
     _compare_layer(c, C, R, layer, out)
+    # materialised x_perm instead of the gather fused into the first GEMM: same bits
+    layer2, out2, _ = _run_layer_gpu(c, C, R, packed=packed, fuse_gather=False)
+    assert torch.equal(fused, out2)
+    K = int(layer2.disp_out["expert_offset"][E].item())
+    perm = layer2.disp_out["perm"][:K].long()
+    assert torch.equal(layer2.disp_out["x_perm"][:K], to_dev(c["x"])[perm])
 
 
 def test_replication_on_and_off_give_identical_outputs_config2():
