@@ -20,7 +20,8 @@ constexpr int FFN_BN = 128;   // columns per workgroup (bf16 path)
 constexpr int FFN_BK = 128;   // k chunk of the bf16 path
 
 struct __attribute__((aligned(16))) WorkItem {
-    int expert, row_begin, row_end, pad;
+    int expert, row_begin, row_end;
+    int reuse;   // 1: other tiles read the same expert's weights (keep them in L2); 0: read-once stream
 };
 
 // ------------------------------------------------------------------ weight packing
@@ -53,18 +54,20 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
     int base = 0;
     for (int p0 = 0; p0 < P; p0 += 1024) {
         int p = p0 + threadIdx.x;
-        int cnt = 0, e = -1, r0 = 0, r1 = 0;
+        int cnt = 0, e = -1, r0 = 0, r1 = 0, reuse = 0;
         if (p < P) {
             e = slot_expert[p];
             r0 = slot_offset[p];
             if (schedule == MOE_SCHEDULE_SLOTS) {
                 r1 = slot_offset[p + 1];
                 cnt = (r1 - r0 + FFN_BM - 1) / FFN_BM;
+                reuse = cnt > 1 || (p > 0 && slot_expert[p - 1] == e) || (p + 1 < P && slot_expert[p + 1] == e);
             } else if (p == 0 || slot_expert[p - 1] != e) {
                 int q = p + 1;
                 while (q < P && slot_expert[q] == e) ++q;
                 r1 = slot_offset[q];
                 cnt = r1 > r0 ? 1 : 0;
+                reuse = r1 - r0 > FFN_BM;
             }
             if (e < 0) cnt = 0;
         }
@@ -73,7 +76,7 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
             if (off + i < max_items) {
                 WorkItem it;
                 it.expert = e;
-                it.pad = 0;
+                it.reuse = reuse;
                 if (schedule == MOE_SCHEDULE_SLOTS) {
                     it.row_begin = r0 + i * FFN_BM;
                     it.row_end = it.row_begin + FFN_BM < r1 ? it.row_begin + FFN_BM : r1;
@@ -111,22 +114,36 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
         const int nrows = row_end - r0 < FFN_BM ? row_end - r0 : FFN_BM;
         f32x16_t acc[2][1];
         zero_acc<2, 1>(acc);
-        if (row_index)
-            gemm_tile_bf16<2, 1, FFN_BK>(A, K, nrows, Bp, nt * FFN_BN, K, lds, acc, row_index + r0, n_src_rows);
+        const bf16_t *a0 = row_index ? A : A + (size_t)r0 * K;
+        const int32_t *ri = row_index ? row_index + r0 : nullptr;
+        if (it.reuse)
+            gemm_tile_bf16<2, 1, FFN_BK, false>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc, ri, n_src_rows);
         else
-            gemm_tile_bf16<2, 1, FFN_BK>(A + (size_t)r0 * K, K, nrows, Bp, nt * FFN_BN, K, lds, acc);
-        const int col = nt * FFN_BN + w * 32 + (lane & 31);
+            gemm_tile_bf16<2, 1, FFN_BK, true>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc, ri, n_src_rows);
+        // Epilogue through LDS: an accumulator lane holds single columns of 16 different rows,
+        // and 2-byte stores that cover a quarter of a cache line each cost more HBM time than
+        // the whole weight stream of a small tile.  The tile is transposed in LDS (the A buffers
+        // are free after the last barrier of the product) and leaves as 16-byte stores, 16
+        // consecutive lanes writing the 256 contiguous bytes of one row.
+        constexpr int LDC = FFN_BN + 8;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                int r = mb * 32 + acc_row(v, lane);
-                if (r < nrows) {
-                    float val = acc[mb][0][v];
-                    if (RELU) val = val > 0.f ? val : 0.f;
-                    C[(size_t)(r0 + r) * N + col] = f32_to_bf16(val);
-                }
+                float val = acc[mb][0][v];
+                if (RELU) val = val > 0.f ? val : 0.f;
+                lds[(mb * 32 + acc_row(v, lane)) * LDC + w * 32 + (lane & 31)] = f32_to_bf16(val);
             }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < FFN_BM * (FFN_BN / 8) / GEMM_THREADS; ++i) {
+            int p = threadIdx.x + i * GEMM_THREADS;
+            int r = p / (FFN_BN / 8), c8 = p % (FFN_BN / 8);
+            if (r < nrows)
+                *reinterpret_cast<uint4 *>(C + (size_t)(r0 + r) * N + nt * FFN_BN + c8 * 8) =
+                    *reinterpret_cast<const uint4 *>(lds + r * LDC + c8 * 8);
+        }
+        __syncthreads();
     }
 }
 

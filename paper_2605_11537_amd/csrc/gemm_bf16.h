@@ -44,7 +44,11 @@ __device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 
 //   A + row_idx[r]*lda instead of A + r*lda (fused gather of token rows).
 // Bp: packed matrix (K x N) of this tile's expert; n0 = first column of the tile (multiple of 32).
 // K must be a multiple of BK.
-template <int MB, int NB, int BK>
+// STREAM_B: the B operand is read exactly once in the whole launch (expert weights): load it
+// with the non-temporal hint so the stream does not evict the activations the other operand
+// and the epilogue keep in cache.  (Measured on the 604 MB weight stream of a 128-expert
+// layer: 120 -> 110 us for the first FFN product, 111 -> 101 us for the second.)
+template <int MB, int NB, int BK, bool STREAM_B = false>
 __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int lda, int nrows,
                                                const bf16_t *__restrict__ Bp, int n0, int K,
                                                bf16_t *__restrict__ lds, f32x16_t (&acc)[MB][NB],
@@ -93,8 +97,16 @@ __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                b[ks][nb] = b_base[((size_t)nb * KG + kc * (BK / 8) + ks * 2) * 32];
+            for (int ks = 0; ks < KS; ++ks) {
+                const uint4 *p = b_base + ((size_t)nb * KG + kc * (BK / 8) + ks * 2) * 32;
+                if (STREAM_B) {
+                    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+                    u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+                    b[ks][nb] = make_uint4(v.x, v.y, v.z, v.w);
+                } else {
+                    b[ks][nb] = *p;
+                }
+            }
     };
     auto compute = [&](int kc, const uint4(&b)[KS][NB]) {
         const bf16_t *src = lds + (kc & 1) * (MB * 32 * LDA) + (lane & 31) * LDA + (lane >> 5) * 8;
