@@ -122,9 +122,10 @@ int sru_predict(const void *emb, const sru_weights *w, int B, int L, int dtype, 
  * Integer-only; ids outside [0,E) are ignored.  E <= MOE_MAX_EXPERTS, E+budget <=
  * MOE_MAX_SLOTS.
  */
+size_t replica_plan_workspace_bytes(int T, int E); /* 0 for small batches: ws may then be NULL */
 int replica_plan(const int32_t *idx, int T, int E, int budget, int slot_capacity, int policy,
                  int32_t *plan_counts, int32_t *replicas, int32_t *slot_base,
-                 int32_t *slot_expert, int32_t *n_slots, void *stream);
+                 int32_t *slot_expert, int32_t *n_slots, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
  * moe_dispatch -- capacity-limited dispatch of tokens to physical slots (Algorithm 1: a token

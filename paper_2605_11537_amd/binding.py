@@ -22,7 +22,7 @@ EXPORTS = (
     "moe_last_error", "moe_version",
     "moe_route_workspace_bytes", "moe_route",
     "sru_predict_workspace_bytes", "sru_predict",
-    "replica_plan",
+    "replica_plan_workspace_bytes", "replica_plan",
     "moe_dispatch_workspace_bytes", "moe_dispatch",
     "moe_packed_weights_bytes", "moe_pack_weights",
     "moe_expert_ffn_workspace_bytes", "moe_expert_ffn", "moe_expert_ffn_set_timing_events",
@@ -62,7 +62,8 @@ def lib():
         _lib.moe_route.argtypes = [P, P, I, P, I, I, I, I, P, P, P, P, S, P]
         _lib.sru_predict_workspace_bytes.argtypes = [C.POINTER(SruWeightsC), I, I, I]
         _lib.sru_predict.argtypes = [P, C.POINTER(SruWeightsC), I, I, I, P, P, P, S, P]
-        _lib.replica_plan.argtypes = [P, I, I, I, I, I, P, P, P, P, P, P]
+        _lib.replica_plan_workspace_bytes.argtypes = [I, I]
+        _lib.replica_plan.argtypes = [P, I, I, I, I, I, P, P, P, P, P, P, S, P]
         _lib.moe_dispatch_workspace_bytes.argtypes = [I, I]
         _lib.moe_dispatch.argtypes = [P, P, P, I, I, I, I, I, I, P, P, P, P, P, P, P, P, S, P]
         _lib.moe_packed_weights_bytes.argtypes = [I, I, I, I]
@@ -161,15 +162,18 @@ def sru_predict(emb, weights: SruWeights, want_logits=False, out=None, ws=None):
     return pred, logits
 
 
-def replica_plan(idx, E, budget, slot_capacity, policy=0, out=None):
+def replica_plan(idx, E, budget, slot_capacity, policy=0, out=None, ws=None):
     """-> dict(plan_counts[E], replicas[E], slot_base[E+1], slot_expert[E+budget], n_slots[1])."""
     dev = idx.device
+    if ws is None:
+        need = lib().replica_plan_workspace_bytes(idx.shape[0], E)
+        ws = _ws(need, dev) if need else None
     o = out if out is not None else dict(plan_counts=_i32(E, dev), replicas=_i32(E, dev),
                                          slot_base=_i32(E + 1, dev), slot_expert=_i32(E + budget, dev),
                                          n_slots=_i32(1, dev))
     _check(lib().replica_plan(_ptr(idx), idx.shape[0], E, budget, slot_capacity, policy, _ptr(o["plan_counts"]),
                               _ptr(o["replicas"]), _ptr(o["slot_base"]), _ptr(o["slot_expert"]),
-                              _ptr(o["n_slots"]), _stream()))
+                              _ptr(o["n_slots"]), _ptr(ws), ws.numel() if ws is not None else 0, _stream()))
     return o
 
 
@@ -249,6 +253,7 @@ class MoeLayer:
         self.route_ws = _ws(L.moe_route_workspace_bytes(T, d, E, dt), dev)
         self.plan_out = dict(plan_counts=_i32(E, dev), replicas=_i32(E, dev), slot_base=_i32(E + 1, dev),
                              slot_expert=_i32(E + budget, dev), n_slots=_i32(1, dev))
+        self.plan_ws = _ws(L.replica_plan_workspace_bytes(T, E), dev)
         self.disp_out = dict(counts=_i32(E, dev), kept=_i32(E, dev), expert_offset=_i32(E + 1, dev),
                              slot_offset=_i32(self.max_slots + 1, dev), perm=_i32(T, dev), inv=_i32(T, dev),
                              x_perm=torch.zeros(T, d, dtype=dtype, device=dev))
@@ -264,7 +269,8 @@ class MoeLayer:
         R = self.R if budget is None else budget
         if R != self.R:
             raise ValueError("budget is fixed by the preallocated slot tables")
-        pl = replica_plan(idx if plan_ids is None else plan_ids, self.E, R, self.C, self.policy, out=self.plan_out)
+        pl = replica_plan(idx if plan_ids is None else plan_ids, self.E, R, self.C, self.policy, out=self.plan_out,
+                          ws=self.plan_ws)
         dp = moe_dispatch(None if fuse_gather else x, idx, pl["replicas"], self.E, self.C, self.max_slots,
                           out=self.disp_out, ws=self.disp_ws, shape=(self.T, self.d), dtype=x.dtype)
         y = moe_expert_ffn(x if fuse_gather else dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"],

@@ -83,30 +83,35 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
     const int base = blockIdx.x * DSP_TOKENS;
     for (int i = tid; i < DSP_CHUNKS * E; i += DSP_THREADS) chunk_cnt[i / E][i % E] = 0;
 
-    // ---- tables (thread t owns experts 4t..4t+3)
+    // ---- tables.  Pass 1: thread per expert (strided), coalesced over the block histograms.
+    for (int e = tid; e < E; e += DSP_THREADS) {
+        int tot = 0, bef = 0;
+#pragma unroll 8
+        for (int b = 0; b < nb; ++b) {
+            int v = block_hist[(size_t)b * E + e];
+            bef += b < (int)blockIdx.x ? v : 0;
+            tot += v;
+        }
+        int r = replicas ? replicas[e] : 1;
+        if (r < 1) r = 1;
+        long long cap = (long long)r * C;
+        before_e[e] = bef;
+        cap_e[e] = (long long)tot < cap ? tot : (int)cap;
+        eoff_e[e] = tot;      // total count, replaced by the offset below
+    }
+    __syncthreads();
+    // Pass 2: thread t owns experts 4t..4t+3 for the scans over experts
     int n4[4], r4[4], k4[4], off4[4], sb4[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int e = tid * 4 + i;
-        int tot = 0, bef = 0;
-        if (e < E) {
-            for (int b = 0; b < nb; ++b) {
-                int v = block_hist[(size_t)b * E + e];
-                bef += b < (int)blockIdx.x ? v : 0;
-                tot += v;
-            }
-        }
+        n4[i] = e < E ? eoff_e[e] : 0;
+        k4[i] = e < E ? cap_e[e] : 0;
         int r = (e < E) ? (replicas ? replicas[e] : 1) : 0;
         if (e < E && r < 1) r = 1;
-        long long cap = (long long)r * C;
-        n4[i] = tot;
         r4[i] = r;
-        k4[i] = (long long)tot < cap ? tot : (int)cap;
-        if (e < E) {
-            before_e[e] = bef;
-            cap_e[e] = k4[i];
-        }
     }
+    __syncthreads();
     block_scan4_256(k4, off4, wave_sums, &total_k);
     block_scan4_256(r4, sb4, wave_sums, &total_p);
     const int K = total_k, P = total_p;

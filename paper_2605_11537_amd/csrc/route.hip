@@ -12,7 +12,6 @@
 
 namespace moe {
 
-constexpr int RT_BM = 32;    // tokens per workgroup: small tiles, many workgroups
 constexpr int RT_BK = 128;
 
 __device__ __forceinline__ void argmax_merge(float &v, int &i, float ov, int oi)
@@ -38,7 +37,10 @@ __global__ __launch_bounds__(256) void pack_matrix_kernel(const bf16_t *__restri
     out[((size_t)(n >> 5) * (K / 8) + kg) * 32 + (n & 31)] = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-template <int NB>
+// MB row blocks of 32 tokens per workgroup: 1 for small batches (many small workgroups hide the
+// k-loop latency), 4 for large ones (every workgroup reads the whole packed router matrix from
+// L2, so fewer, taller tiles cut that traffic).
+template <int NB, int MB>
 __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *__restrict__ x,
                                                                   const bf16_t *__restrict__ wr_packed,
                                                                   const float *__restrict__ bias, int T, int d,
@@ -47,21 +49,26 @@ __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *
 {
     constexpr int E = NB * 128;
     constexpr int LDL = E + 4;
-    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<1, RT_BK>()];
-    __shared__ float tile[32 * LDL];
+    constexpr int RT_BM = MB * 32;
+    constexpr int BK = MB == 4 ? 64 : RT_BK;      // keeps the staging buffers under 64 KB
+    constexpr int STAGE_BYTES = gemm_lds_elems<MB, BK>() * 2, TILE_BYTES = 32 * LDL * 4;
+    // the logits tile reuses the A staging buffers, which are free once the product is done
+    __shared__ __attribute__((aligned(16))) char smem[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
+    bf16_t *lds = reinterpret_cast<bf16_t *>(smem);
+    float *tile = reinterpret_cast<float *>(smem);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int row0 = blockIdx.x * RT_BM;
     const int nrows = T - row0 < RT_BM ? T - row0 : RT_BM;
-    f32x16_t acc[1][NB];
-    zero_acc<1, NB>(acc);
-    gemm_tile_bf16<1, NB, RT_BK>(x + (size_t)row0 * d, d, nrows, wr_packed, 0, d, lds, acc);
+    f32x16_t acc[MB][NB];
+    zero_acc<MB, NB>(acc);
+    gemm_tile_bf16<MB, NB, BK>(x + (size_t)row0 * d, d, nrows, wr_packed, 0, d, lds, acc);
 
     float b[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) b[nb] = bias ? bias[(w * NB + nb) * 32 + (lane & 31)] : 0.f;
 
-    constexpr int mb = 0;
-    {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -176,13 +183,21 @@ int route_launch(const void *x, const void *w_router, int w_layout, const float 
             if (rc != MOE_OK) return rc;
             wp = ws;
         }
-        int grid = ceil_div(T, RT_BM);
-        if (E == 128)
-            hipLaunchKernelGGL(route_mfma_kernel<1>, dim3(grid), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x,
-                               (const bf16_t *)wp, b_router, T, d, idx, prob, logits_opt);
-        else
-            hipLaunchKernelGGL(route_mfma_kernel<2>, dim3(grid), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x,
-                               (const bf16_t *)wp, b_router, T, d, idx, prob, logits_opt);
+        const int mbk = T <= 8192 ? 1 : T <= 32768 ? 2 : 4;
+        int grid = ceil_div(T, 32 * mbk);
+#define MOE_ROUTE_LAUNCH(NB_, MB_)                                                                            \
+    hipLaunchKernelGGL((route_mfma_kernel<NB_, MB_>), dim3(grid), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x, \
+                       (const bf16_t *)wp, b_router, T, d, idx, prob, logits_opt)
+        if (E == 128) {
+            if (mbk == 1) MOE_ROUTE_LAUNCH(1, 1);
+            else if (mbk == 2) MOE_ROUTE_LAUNCH(1, 2);
+            else MOE_ROUTE_LAUNCH(1, 4);
+        } else {
+            if (mbk == 1) MOE_ROUTE_LAUNCH(2, 1);
+            else if (mbk == 2) MOE_ROUTE_LAUNCH(2, 2);
+            else MOE_ROUTE_LAUNCH(2, 4);
+        }
+#undef MOE_ROUTE_LAUNCH
     } else if (dtype == MOE_BF16) {
         hipLaunchKernelGGL(route_generic_kernel<true>, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, w_router, b_router, T,
                            d, E, idx, prob, logits_opt);

@@ -58,10 +58,13 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.moe_route(p, p, 0, None, 4, 768, 128, 1, p, p, None, p, 16, None) == WS
     assert b"workspace" in L.moe_last_error()
     # replica_plan
-    assert L.replica_plan(p, 4, 8, -1, 1, 0, p, p, p, p, p, None) == INV
-    assert L.replica_plan(p, 4, 8, 2, 0, 0, p, p, p, p, p, None) == INV
-    assert L.replica_plan(p, 4, 8, 2, 1, 3, p, p, p, p, p, None) == INV
-    assert L.replica_plan(p, 4, 4096, 2, 1, 0, p, p, p, p, p, None) == UNS
+    assert L.replica_plan(p, 4, 8, -1, 1, 0, p, p, p, p, p, None, 0, None) == INV
+    assert L.replica_plan(p, 4, 8, 2, 0, 0, p, p, p, p, p, None, 0, None) == INV
+    assert L.replica_plan(p, 4, 8, 2, 1, 3, p, p, p, p, p, None, 0, None) == INV
+    assert L.replica_plan(p, 4, 4096, 2, 1, 0, p, p, p, p, p, None, 0, None) == UNS
+    assert L.replica_plan(p, 65536, 256, 2, 1, 0, p, p, p, p, p, None, 0, None) == WS
+    assert L.replica_plan_workspace_bytes(4096, 128) == 0
+    assert L.replica_plan_workspace_bytes(65536, 256) >= 8 * 256 * 4
     # moe_dispatch
     assert L.moe_dispatch(p, p, None, 4, 64, 8, 0, 8, 0, p, p, p, p, p, p, p, p, 4096, None) == INV  # C = 0
     assert L.moe_dispatch(p, p, None, 4, 6, 8, 1, 8, 0, p, p, p, p, p, p, p, p, 4096, None) == INV   # row bytes

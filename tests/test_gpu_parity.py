@@ -38,7 +38,8 @@ def _sync():
 def test_plan_bit_exact_random(policy):
     rng = np.random.default_rng(40 + policy)
     cases = [(0, 4, 3, 2), (1, 1, 0, 1), (700, 8, 4, 80), (4096, 128, 16, 40), (5000, 100, 37, 7),
-             (16384, 256, 32, 64), (3000, 1024, 100, 2), (2048, 64, 4000, 1), (777, 3, 0, 5)]
+             (16384, 256, 32, 64), (3000, 1024, 100, 2), (2048, 64, 4000, 1), (777, 3, 0, 5),
+             (8193, 7, 3, 300), (70001, 300, 64, 128)]
     for T, E, R, C in cases:
         p = rng.dirichlet(np.ones(E) * 0.2)
         ids = rng.choice(E, size=T, p=p).astype(np.int32)
