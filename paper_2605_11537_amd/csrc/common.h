@@ -66,6 +66,39 @@ __device__ __forceinline__ int xcd_remap(int bid, int n_valid)
     return (slot < per && lid < n_valid) ? lid : -1;
 }
 
+// Workgroup id -> (item, column tile) for a grouped GEMM over n_items row tiles x n_nt column
+// tiles, XCD-aware (consecutive hardware workgroup ids go to the 8 XCDs in turn).
+//   group == 0: the n_items*n_nt tiles are cut into 8 contiguous ranges, one per XCD.  Every
+//     tile costs the same when the weight stream binds, so this balances exactly, and the
+//     column tiles of an item (which share its token rows) meet in one L2.
+//   group  > 0: items are dealt to the XCDs in chunks of `group` consecutive items, and inside
+//     a chunk the order is column-tile-major.  The workgroups resident on an XCD then share
+//     one 32-column-strip set of weights and `group` row tiles, both far below the L2 size,
+//     so a hot expert's weights are not re-fetched for each of its hundreds of row tiles; and
+//     its tiles spread over all XCDs.
+// The grid must hold 8*ceil(ceil(n_items/group)/8)*group*n_nt workgroups in the second case.
+__device__ __forceinline__ bool grouped_tile_of(int bid, int n_items, int n_nt, int group, int &item, int &nt)
+{
+    if (group <= 0) {
+        int lid = xcd_remap(bid, n_items * n_nt);
+        if (lid < 0) return false;
+        item = lid / n_nt;
+        nt = lid - item * n_nt;
+        return true;
+    }
+    const int per_chunk = group * n_nt;
+    const int j = bid >> 3;                        // index among this XCD's workgroups
+    const int chunk = (j / per_chunk) * 8 + (bid & 7);
+    const int within = j % per_chunk;
+    const int first = chunk * group;
+    if (first >= n_items) return false;
+    const int g = n_items - first < group ? n_items - first : group;   // items in this chunk
+    if (within >= g * n_nt) return false;
+    nt = within / g;
+    item = first + within % g;
+    return true;
+}
+
 // Exclusive scan of one int per thread over a 1024-thread workgroup.  Returns the prefix and
 // leaves the grand total in *total_out (LDS).  wave_sums is LDS scratch of 16 ints.
 __device__ __forceinline__ int block_scan_excl_1024(int v, int *wave_sums, int *total_out)

@@ -18,6 +18,8 @@ namespace moe {
 constexpr int FFN_BM = 64;    // rows per tile
 constexpr int FFN_BN = 128;   // columns per workgroup (bf16 path)
 constexpr int FFN_BK = 128;   // k chunk of the bf16 path
+constexpr int FFN_GROUP = 16;            // row tiles per chunk of the grouped order
+constexpr int FFN_GROUP_MIN_ITEMS = 512; // below this many row tiles the weight stream binds: contiguous order
 
 struct __attribute__((aligned(16))) WorkItem {
     int expert, row_begin, row_end;
@@ -44,8 +46,8 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restr
 __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__restrict__ slot_offset,
                                                             const int32_t *__restrict__ slot_expert,
                                                             const int32_t *__restrict__ n_slots_p, int max_slots,
-                                                            int max_items, int schedule, WorkItem *__restrict__ items,
-                                                            int32_t *__restrict__ n_items)
+                                                            int max_items, int schedule, int tile_rows,
+                                                            WorkItem *__restrict__ items, int32_t *__restrict__ n_items)
 {
     __shared__ int wave_sums[16];
     __shared__ int total;
@@ -60,14 +62,14 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
             r0 = slot_offset[p];
             if (schedule == MOE_SCHEDULE_SLOTS) {
                 r1 = slot_offset[p + 1];
-                cnt = (r1 - r0 + FFN_BM - 1) / FFN_BM;
+                cnt = (r1 - r0 + tile_rows - 1) / tile_rows;
                 reuse = cnt > 1 || (p > 0 && slot_expert[p - 1] == e) || (p + 1 < P && slot_expert[p + 1] == e);
             } else if (p == 0 || slot_expert[p - 1] != e) {
                 int q = p + 1;
                 while (q < P && slot_expert[q] == e) ++q;
                 r1 = slot_offset[q];
                 cnt = r1 > r0 ? 1 : 0;
-                reuse = r1 - r0 > FFN_BM;
+                reuse = r1 - r0 > tile_rows;
             }
             if (e < 0) cnt = 0;
         }
@@ -78,8 +80,8 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
                 it.expert = e;
                 it.reuse = reuse;
                 if (schedule == MOE_SCHEDULE_SLOTS) {
-                    it.row_begin = r0 + i * FFN_BM;
-                    it.row_end = it.row_begin + FFN_BM < r1 ? it.row_begin + FFN_BM : r1;
+                    it.row_begin = r0 + i * tile_rows;
+                    it.row_end = it.row_begin + tile_rows < r1 ? it.row_begin + tile_rows : r1;
                 } else {
                     it.row_begin = r0;
                     it.row_end = r1;
@@ -90,7 +92,12 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
         base += total;
         __syncthreads();
     }
-    if (threadIdx.x == 0) n_items[0] = base < max_items ? base : max_items;
+    if (threadIdx.x == 0) {
+        int n = base < max_items ? base : max_items;
+        n_items[0] = n;
+        // many row tiles = long slots: chunked, column-tile-major order (see grouped_tile_of)
+        n_items[1] = n >= FFN_GROUP_MIN_ITEMS ? FFN_GROUP : 0;
+    }
 }
 
 // ------------------------------------------------------------------ bf16 grouped GEMM
@@ -102,9 +109,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
 {
     __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2, FFN_BK>()];
     const int n_nt = N / FFN_BN;
-    const int lid = xcd_remap(blockIdx.x, n_items[0] * n_nt);
-    if (lid < 0) return;
-    const int item = lid / n_nt, nt = lid - item * n_nt;
+    int item, nt;
+    if (!grouped_tile_of(blockIdx.x, n_items[0], n_nt, n_items[1], item, nt)) return;
     const WorkItem it = items[item];
     if (it.expert < 0 || it.expert >= E || it.row_begin < 0) return;  // never index weights with a bad id
     const bf16_t *Bp = Wp + (size_t)it.expert * K * N;
@@ -308,16 +314,20 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
     p += align_up((size_t)max_items * sizeof(WorkItem), 256);
     int32_t *n_items = (int32_t *)p;
 
+    const int tile_rows = FFN_BM;
     hipLaunchKernelGGL(ffn_worklist_kernel, dim3(1), dim3(1024), 0, st, slot_offset, slot_expert, n_slots, max_slots,
-                       max_items, schedule, items, n_items);
+                       max_items, schedule, tile_rows, items, n_items);
     MOE_CHECK_LAUNCH("moe_expert_ffn/worklist");
-    int grid_items = schedule == MOE_SCHEDULE_SLOTS ? max_items : (max_slots < max_items ? max_slots : max_items);
+    int grid_items = schedule == MOE_SCHEDULE_SLOTS ? max_slots + max_rows / tile_rows + 1
+                                                    : (max_slots < max_items ? max_slots : max_items);
     hipEvent_t ev[3] = {g_timing_ev[0], g_timing_ev[1], g_timing_ev[2]};
     g_timing_ev[0] = g_timing_ev[1] = g_timing_ev[2] = nullptr;
     if (ev[0]) (void)hipEventRecord(ev[0], st);
     if (dtype == MOE_BF16) {
-        int g1 = (int)align_up((size_t)grid_items * (F / FFN_BN), 8);
-        int g2 = (int)align_up((size_t)grid_items * (d / FFN_BN), 8);
+        // worst case of both orders: chunks of FFN_GROUP items, rounded up to 8 chunks
+        size_t gi = align_up((size_t)ceil_div(grid_items, FFN_GROUP), 8) * FFN_GROUP;
+        int g1 = (int)(gi * (F / FFN_BN));
+        int g2 = (int)(gi * (d / FFN_BN));
         hipLaunchKernelGGL(ffn_gemm_bf16_kernel<true>, dim3(g1), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x_perm,
                            row_index, max_rows, (const bf16_t *)w1, d, F, E, items, n_items, max_rows, (bf16_t *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");

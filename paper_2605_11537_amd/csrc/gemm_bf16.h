@@ -14,8 +14,11 @@
 // HBM straight into registers exactly once per workgroup, in DRAM-page order, and never
 // pass through LDS.
 //
-// One workgroup = 4 wavefronts.  Wavefront w owns NB column strips (columns
-// n0 + (w*NB + nb)*32 ..) and all MB row blocks of 32 rows: MB*NB accumulators of 16 VGPRs.
+// One workgroup = 4 wavefronts arranged WM x WN (WN = 4 / WM).  Wavefront (wm, wn) owns MB row
+// blocks of 32 rows (rows (wm*MB + mb)*32 ..) and NB column strips (columns
+// n0 + (wn*NB + nb)*32 ..): MB*NB accumulators of 16 VGPRs.  WM = 1 is the weight-streaming
+// shape (every weight byte is loaded by exactly one wavefront); WM = 2 doubles the rows per
+// weight byte for compute-bound tiles.
 // The A rows (tokens) are shared by the four wavefronts and staged through LDS in BK-wide k
 // chunks, double buffered; the global loads of chunk i+1 (A and B) are issued before the
 // matrix instructions of chunk i, B registers ping-pong between two sets so nothing is
@@ -30,10 +33,10 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int GEMM_THREADS = 256;
 
-template <int MB, int BK>
+template <int MB, int BK, int WM = 1>
 constexpr int gemm_lds_elems()
 {
-    return 2 * MB * 32 * (BK + 8);   // row stride BK+8 elements keeps the b128 reads conflict free
+    return 2 * WM * MB * 32 * (BK + 8);   // row stride BK+8 elements keeps the b128 reads conflict free
 }
 
 // Row of accumulator register v (0..15) of a 32x32 block for this lane; its column is lane & 31.
@@ -48,7 +51,7 @@ __device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 
 // with the non-temporal hint so the stream does not evict the activations the other operand
 // and the epilogue keep in cache.  (Measured on the 604 MB weight stream of a 128-expert
 // layer: 120 -> 110 us for the first FFN product, 111 -> 101 us for the second.)
-template <int MB, int NB, int BK, bool STREAM_B = false>
+template <int MB, int NB, int BK, bool STREAM_B = false, int WM = 1>
 __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int lda, int nrows,
                                                const bf16_t *__restrict__ Bp, int n0, int K,
                                                bf16_t *__restrict__ lds, f32x16_t (&acc)[MB][NB],
@@ -56,18 +59,21 @@ __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int
 {
     constexpr int LDA = BK + 8;
     constexpr int KS = BK / 16;                       // 16-deep MFMA steps per chunk
-    constexpr int PIECES = MB * 32 * (BK / 8);        // 16-byte pieces of one A chunk
+    constexpr int WN = 4 / WM;
+    constexpr int BM = WM * MB * 32;                  // rows of the workgroup tile
+    constexpr int PIECES = BM * (BK / 8);             // 16-byte pieces of one A chunk
     constexpr int A_PER_THREAD = PIECES / GEMM_THREADS;
     constexpr int ROW_STEP = GEMM_THREADS / (BK / 8);
     static_assert(PIECES % GEMM_THREADS == 0, "A chunk must split evenly over the workgroup");
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wm = w / WN, wn = w % WN;
     const int nk = K / BK;
     const int KG = K >> 3;
     uint4 a_reg[A_PER_THREAD];
     uint4 b0[KS][NB], b1[KS][NB];
     const int a_col = tid % (BK / 8);
     const int a_row = tid / (BK / 8);
-    const uint4 *b_base = reinterpret_cast<const uint4 *>(Bp) + (size_t)((n0 >> 5) + w * NB) * KG * 32 + lane;
+    const uint4 *b_base = reinterpret_cast<const uint4 *>(Bp) + (size_t)((n0 >> 5) + wn * NB) * KG * 32 + lane;
 
     const bf16_t *a_src[A_PER_THREAD];   // this thread's rows stay the same for every k chunk
     bool a_ok[A_PER_THREAD];             // rows past the tile, or an index outside the source, read as 0
@@ -88,7 +94,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int
             a_reg[i] = a_ok[i] ? *reinterpret_cast<const uint4 *>(a_src[i] + kc * BK) : make_uint4(0, 0, 0, 0);
     };
     auto store_a = [&](int buf) {
-        bf16_t *dst = lds + buf * (MB * 32 * LDA);
+        bf16_t *dst = lds + buf * (BM * LDA);
 #pragma unroll
         for (int i = 0; i < A_PER_THREAD; ++i)
             *reinterpret_cast<uint4 *>(dst + (a_row + i * ROW_STEP) * LDA + a_col * 8) = a_reg[i];
@@ -109,7 +115,7 @@ __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int
             }
     };
     auto compute = [&](int kc, const uint4(&b)[KS][NB]) {
-        const bf16_t *src = lds + (kc & 1) * (MB * 32 * LDA) + (lane & 31) * LDA + (lane >> 5) * 8;
+        const bf16_t *src = lds + (kc & 1) * (BM * LDA) + (wm * MB * 32 + (lane & 31)) * LDA + (lane >> 5) * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll

@@ -211,6 +211,34 @@ def test_ffn_bf16_ragged_slots(schedule):
     assert (np.abs(g - r) <= 2.0 ** -7 * np.abs(r) + 1e-3 * np.abs(r).max()).all()
 
 
+@pytest.mark.parametrize("schedule", [0, 1])
+def test_ffn_bf16_long_slots(schedule):
+    """Few long slots spanning many row tiles; ragged row counts around the tile height, an
+    empty slot, and the fused gather."""
+    E, d, F = 3, 256, 512
+    rows = [300, 129, 0, 128, 1, 700]
+    experts = [0, 0, 1, 1, 2, 2]
+    so, se = _slots_for(rows, experts)
+    K = int(so[-1])
+    T = K + 5
+    x = synth.normal_tensor((T, d), 1.0, [21], synth.BF16)
+    w1 = synth.normal_tensor((E, d, F), 0.05, [22], synth.BF16)
+    w2 = synth.normal_tensor((E, F, d), 0.05, [23], synth.BF16)
+    ref = oracle.ffn(x, w1, w2, so, se, len(rows))
+    args = (moe.moe_pack_weights(to_dev(w1)), moe.moe_pack_weights(to_dev(w2)), to_dev(so), to_dev(se),
+            torch.tensor([len(rows)], dtype=torch.int32, device="cuda"), E, F)
+    y = moe.moe_expert_ffn(to_dev(x), *args, schedule=schedule)
+    assert_close(to_host(y)[:K], ref[:K], synth.BF16, "ffn bf16 large tiles")
+    g, r = f64(to_host(y)[:K]), f64(ref[:K])
+    assert (np.abs(g - r) <= 2.0 ** -7 * np.abs(r) + 1e-3 * np.abs(r).max()).all()
+    # fused gather: rows arrive through an index
+    perm = np.random.default_rng(1).permutation(T).astype(np.int32)
+    x_src = np.zeros_like(x)
+    x_src[perm] = x
+    y2 = moe.moe_expert_ffn(to_dev(x_src), *args, schedule=schedule, row_index=to_dev(perm))
+    assert torch.equal(y[:K], y2[:K])
+
+
 # --------------------------------------------------------------------------- whole layer
 def _run_layer_gpu(c, C, R, schedule=0, residual=0, plan_ids=None, packed=None, fuse_gather=True):
     dt = torch.bfloat16 if c["dtype"] == synth.BF16 else torch.float32
