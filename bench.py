@@ -7,7 +7,7 @@ sru_predict in front, its ids driving the plan).  Default workload: the Switch-b
 layer (T=4096, d=768, F=3072, E=128, capacity factor 1.25, replica budget 16, bf16 with fp32
 accumulation), Zipf(1.0)-skewed routing.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg4|cfg4b|cfg5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg4b|cfg5]
 """
 from __future__ import annotations
 
@@ -39,6 +39,12 @@ def _workload(name):
     if name == "cfg2":
         c = synth.config_inputs(2)
         return c, c["C"], "Switch-base-128 layer T=4096 d=768 F=3072 E=128 CF=1.25 R=16 Zipf(1.0)"
+    if name == "cfg3":
+        # the predictor runs in front of the workload-2 layer and its ids drive the replica plan
+        c = synth.config_inputs(2)
+        c["sru"] = synth.config_inputs(3)["sru"]
+        return c, c["C"], ("2-layer SRU predictor (B=8 L=512 768->256, head 128) + Switch-base-128 layer "
+                           "T=4096 d=768 F=3072 E=128 CF=1.25 R=16")
     if name == "cfg4":
         c = synth.config_inputs(4)
         return c, c["C"], "Switch-base-256 layer T=16384 d=768 F=3072 E=256 CF=1.0 R=32 Zipf(1.1)"
@@ -127,6 +133,16 @@ def main():
 
     layer = moe.MoeLayer(T, d, F, E, R, C, dt)
     layer0 = moe.MoeLayer(T, d, F, E, 0, C, dt)          # budget 0: the plain Switch layer
+    sru = None
+    if "sru" in c:
+        s_ = c["sru"]
+        sru_w = moe.SruWeights([_to_dev(w) for w in s_["w_cat"]], None, None, _to_dev(s_["w_head"]), None, pack=True)
+        emb = _to_dev(s_["emb"])
+        pred = torch.empty(T, dtype=torch.int32, device="cuda")
+        sru_ws = torch.empty(moe.lib().sru_predict_workspace_bytes(__import__("ctypes").byref(sru_w.c), s_["B"],
+                                                                   s_["L"], moe.MOE_BF16), dtype=torch.uint8,
+                             device="cuda")
+        sru = (emb, sru_w, pred, sru_ws)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
     for trio in evs:
         for e in trio:
@@ -134,10 +150,14 @@ def main():
     it = {"i": 0, "timed": False}
 
     def step_on():
+        plan_ids = None
+        if sru is not None:
+            plan_ids, _ = moe.sru_predict(sru[0], sru[1], out=sru[2], ws=sru[3])
         if it["timed"]:
             moe.set_ffn_timing_events(*evs[it["i"]])
             it["i"] += 1
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED)
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED,
+                      plan_ids=plan_ids)
 
     def step_off_same_plan():
         layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=moe.LAYOUT_PACKED)

@@ -92,6 +92,8 @@ int moe_route(const void *x, const void *w_router, int w_layout, const float *b_
  */
 typedef struct sru_weights {
     int n_layers, n_in, n_hidden, n_out;
+    int w_layout; /* MOE_LAYOUT_PLAIN, or MOE_LAYOUT_PACKED: every w_cat[l] and w_head is the image
+                     moe_pack_weights writes for it as a [1, K, N] tensor (n_out = 128 or 256 only) */
     const void *const *w_cat;
     const float *const *b_f;
     const float *const *b_r;

@@ -38,7 +38,7 @@ class MoeError(RuntimeError):
 
 class SruWeightsC(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("n_in", C.c_int), ("n_hidden", C.c_int), ("n_out", C.c_int),
-                ("w_cat", C.POINTER(C.c_void_p)), ("b_f", C.POINTER(C.c_void_p)),
+                ("w_layout", C.c_int), ("w_cat", C.POINTER(C.c_void_p)), ("b_f", C.POINTER(C.c_void_p)),
                 ("b_r", C.POINTER(C.c_void_p)), ("w_head", C.c_void_p), ("b_head", C.c_void_p)]
 
 
@@ -128,7 +128,12 @@ def moe_route(x, w_router, b_router=None, want_logits=False, out=None, ws=None, 
 class SruWeights:
     """Holds the device tensors of an SRU predictor and the host-side C struct naming them."""
 
-    def __init__(self, w_cat, b_f, b_r, w_head, b_head=None):
+    def __init__(self, w_cat, b_f, b_r, w_head, b_head=None, pack=False):
+        """pack=True re-lays the (static) weights once with moe_pack_weights, so that sru_predict
+        does not have to do it on every call (needs n_out = 128 or 256)."""
+        if pack:
+            w_cat = [moe_pack_weights(w[None].contiguous())[0] for w in w_cat]
+            w_head = moe_pack_weights(w_head[None].contiguous())[0]
         self.tensors = (list(w_cat), list(b_f) if b_f else None, list(b_r) if b_r else None, w_head, b_head)
         n = len(w_cat)
         self.n_layers = n
@@ -138,7 +143,7 @@ class SruWeights:
         self._wc = PT(*[w.data_ptr() for w in w_cat])
         self._bf = PT(*[(b.data_ptr() if b is not None else None) for b in b_f]) if b_f else None
         self._br = PT(*[(b.data_ptr() if b is not None else None) for b in b_r]) if b_r else None
-        self.c = SruWeightsC(n, self.n_in, self.n_hidden, self.n_out,
+        self.c = SruWeightsC(n, self.n_in, self.n_hidden, self.n_out, LAYOUT_PACKED if pack else LAYOUT_PLAIN,
                              C.cast(self._wc, C.POINTER(C.c_void_p)),
                              C.cast(self._bf, C.POINTER(C.c_void_p)) if self._bf else None,
                              C.cast(self._br, C.POINTER(C.c_void_p)) if self._br else None,

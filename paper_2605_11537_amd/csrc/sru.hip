@@ -4,17 +4,20 @@
 // MFMA B operand wants (small, into the workspace); (2) one matrix-core product
 // U = X * [W | W_f | W_r | (W_h)] for all B*L tokens at once (the part of the SRU that is
 // parallel over time); (3) the recurrence.  The gates depend on the input only, so
-// c_t = f_t c_{t-1} + (1-f_t) x'_t is a linear recurrence in c: a workgroup takes 64 channels
-// of one sequence and cuts the time axis into 16 chunks, one wavefront each; every wavefront
-// first composes its chunk into (A, B) with c_out = A c_in + B, the carries are chained
-// through LDS, and each wavefront then re-runs its chunk from its true carry-in and writes
-// h_t.  The head is a router-shaped product + argmax and reuses that kernel.
+// c_t = f_t c_{t-1} + (1-f_t) x'_t is a linear recurrence in c: a workgroup takes 16 channels
+// of one sequence and cuts the time axis into 64 chunks; every thread first composes its
+// chunk into (A, B) with c_out = A c_in + B, the carries are chained through LDS, and each
+// thread then re-runs its chunk from its true carry-in and writes h_t (B * n_h * 64 threads,
+// enough to cover the chip at 8 sequences x 256 channels).  The head is a router-shaped
+// product + argmax and reuses that kernel.  Static weights may arrive already packed
+// (sru_weights.w_layout), which removes the per-call re-layout kernels.
 #include "gemm_bf16.h"
 #include "route.h"
 
 namespace moe {
 
-constexpr int SRU_CHUNKS = 16;
+constexpr int SRU_CHUNKS = 64;     // time chunks per sequence
+constexpr int SRU_CHANNELS = 16;   // channels per workgroup (SRU_CHUNKS * SRU_CHANNELS = 1024 threads)
 
 // U[T, N] (fp32) = X[T, K] (bf16) * packed W
 __global__ __launch_bounds__(GEMM_THREADS) void sru_proj_kernel(const bf16_t *__restrict__ X,
@@ -40,22 +43,29 @@ __global__ __launch_bounds__(GEMM_THREADS) void sru_proj_kernel(const bf16_t *__
         }
 }
 
-__device__ __forceinline__ float sigmoidf_(float v) { return 1.f / (1.f + expf(-v)); }
-
-// grid (n_h/64, B); block 64 channels x SRU_CHUNKS time chunks
-__global__ __launch_bounds__(64 * SRU_CHUNKS) void sru_scan_kernel(const float *__restrict__ U,
-                                                                   const bf16_t *__restrict__ x_in, int L, int n_h,
-                                                                   int k, const float *__restrict__ b_f,
-                                                                   const float *__restrict__ b_r,
-                                                                   bf16_t *__restrict__ h_out)
+// binary32 with the hardware exponential: a few ulp, far inside the bf16 rounding of h
+__device__ __forceinline__ float sigmoidf_(float v) { return 1.f / (1.f + __expf(-v)); }
+__device__ __forceinline__ float tanhf_(float v)
 {
-    __shared__ float carry_a[SRU_CHUNKS][64], carry_b[SRU_CHUNKS][64];
-    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
-    const int j = blockIdx.x * 64 + lane;
+    float a = fminf(fabsf(v), 15.f);
+    float t = 1.f - 2.f / (1.f + __expf(2.f * a));
+    return copysignf(t, v);
+}
+
+// grid (n_h/16, B); block = 16 channels x 64 time chunks.  Phase 1: every thread composes its
+// chunk into (A, B) with c_out = A*c_in + B.  Phase 2: one thread per channel chains the 64
+// carries.  Phase 3: every thread re-runs its chunk from its true carry-in and writes h_t.
+__global__ __launch_bounds__(SRU_CHUNKS * SRU_CHANNELS) void sru_scan_kernel(
+    const float *__restrict__ U, const bf16_t *__restrict__ x_in, int L, int n_h, int k,
+    const float *__restrict__ b_f, const float *__restrict__ b_r, bf16_t *__restrict__ h_out)
+{
+    __shared__ float carry_a[SRU_CHUNKS][SRU_CHANNELS], carry_b[SRU_CHUNKS][SRU_CHANNELS];
+    const int ch = threadIdx.x & (SRU_CHANNELS - 1), q = threadIdx.x / SRU_CHANNELS;
+    const int j = blockIdx.x * SRU_CHANNELS + ch;
     const int b = blockIdx.y;
     const int ncol = k * n_h;
     const int cl = (L + SRU_CHUNKS - 1) / SRU_CHUNKS;
-    const int t0 = q * cl, t1 = (t0 + cl < L) ? t0 + cl : L;
+    const int t0 = q * cl < L ? q * cl : L, t1 = (t0 + cl < L) ? t0 + cl : L;
     const float bf = b_f ? b_f[j] : 0.f, br = b_r ? b_r[j] : 0.f;
     const float *u = U + (size_t)b * L * ncol + j;
 
@@ -67,11 +77,19 @@ __global__ __launch_bounds__(64 * SRU_CHUNKS) void sru_scan_kernel(const float *
         a *= f;
         c = f * c + (1.f - f) * ut[0];
     }
-    carry_a[q][lane] = a;
-    carry_b[q][lane] = c;
+    carry_a[q][ch] = a;
+    carry_b[q][ch] = c;
     __syncthreads();
-    c = 0.f;
-    for (int p = 0; p < q; ++p) c = carry_a[p][lane] * c + carry_b[p][lane];
+    if (q == 0) {   // carry-in of every chunk of this channel, in place: carry_b[p] <- state entering chunk p
+        float run = 0.f;
+        for (int p = 0; p < SRU_CHUNKS; ++p) {
+            float na = carry_a[p][ch], nb = carry_b[p][ch];
+            carry_b[p][ch] = run;
+            run = na * run + nb;
+        }
+    }
+    __syncthreads();
+    c = carry_b[q][ch];
 
     const bf16_t *xi = x_in + (size_t)b * L * n_h + j;   // only read when k == 3 (n_in == n_h)
     bf16_t *ho = h_out + (size_t)b * L * n_h + j;
@@ -82,7 +100,7 @@ __global__ __launch_bounds__(64 * SRU_CHUNKS) void sru_scan_kernel(const float *
         float r = sigmoidf_(ut[2 * n_h] + br);
         c = f * c + (1.f - f) * ut[0];
         float hw = k == 4 ? ut[3 * n_h] : bf16_to_f32(xi[(size_t)t * n_h]);
-        ho[(size_t)t * n_h] = f32_to_bf16(r * tanhf(c) + (1.f - r) * hw);
+        ho[(size_t)t * n_h] = f32_to_bf16(r * tanhf_(c) + (1.f - r) * hw);
     }
 }
 
@@ -126,6 +144,11 @@ static int sru_check(const sru_weights *w, int B, int L, int dtype)
     MOE_REQUIRE(w->n_out <= MOE_MAX_EXPERTS && w->n_out % 8 == 0, MOE_ERR_UNSUPPORTED,
                 "sru_predict: n_out=%d must be a multiple of 8 and at most %d", w->n_out, MOE_MAX_EXPERTS);
     MOE_REQUIRE(B <= 65535, MOE_ERR_UNSUPPORTED, "sru_predict: B=%d exceeds 65535", B);
+    MOE_REQUIRE(w->w_layout == MOE_LAYOUT_PLAIN || w->w_layout == MOE_LAYOUT_PACKED, MOE_ERR_INVALID_ARG,
+                "sru_predict: unknown weight layout %d", w->w_layout);
+    MOE_REQUIRE(w->w_layout == MOE_LAYOUT_PLAIN ||
+                    ((w->n_out == 128 || w->n_out == 256) && w->n_hidden % 128 == 0),
+                MOE_ERR_UNSUPPORTED, "sru_predict: packed weights need n_out = 128 or 256");
     return MOE_OK;
 }
 
@@ -159,23 +182,30 @@ extern "C" int sru_predict(const void *emb, const sru_weights *w, int B, int L, 
     bf16_t *hbuf[2] = {(bf16_t *)(base + lay.h0), (bf16_t *)(base + lay.h1)};
     void *wp = base + lay.wp;
     const int T = B * L, n_h = w->n_hidden;
+    // a packed head is only usable by the matrix-core head kernel; otherwise the head stays plain
+    const int head_layout = w->w_layout;
     const bf16_t *cur = (const bf16_t *)emb;
     int nin = w->n_in;
     for (int l = 0; l < w->n_layers; ++l) {
         int k = nin == n_h ? 3 : 4;
         int ncol = k * n_h;
-        rc = pack_matrix_launch(w->w_cat[l], nin, ncol, wp, st, "sru_predict/pack");
-        if (rc != MOE_OK) return rc;
+        const void *wl = w->w_cat[l];
+        if (w->w_layout == MOE_LAYOUT_PLAIN) {
+            rc = pack_matrix_launch(w->w_cat[l], nin, ncol, wp, st, "sru_predict/pack");
+            if (rc != MOE_OK) return rc;
+            wl = wp;
+        }
         hipLaunchKernelGGL(sru_proj_kernel, dim3(ceil_div(T, 64) * (ncol / 128)), dim3(GEMM_THREADS), 0, st, cur,
-                           (const bf16_t *)wp, T, nin, ncol, U);
+                           (const bf16_t *)wl, T, nin, ncol, U);
         MOE_CHECK_LAUNCH("sru_predict/proj");
         bf16_t *out = hbuf[l & 1];
-        hipLaunchKernelGGL(sru_scan_kernel, dim3(n_h / 64, B), dim3(64 * SRU_CHUNKS), 0, st, U, cur, L, n_h, k,
+        hipLaunchKernelGGL(sru_scan_kernel, dim3(n_h / SRU_CHANNELS, B), dim3(SRU_CHUNKS * SRU_CHANNELS), 0, st, U, cur, L,
+                           n_h, k,
                            w->b_f ? w->b_f[l] : nullptr, w->b_r ? w->b_r[l] : nullptr, out);
         MOE_CHECK_LAUNCH("sru_predict/scan");
         cur = out;
         nin = n_h;
     }
-    return route_launch(cur, w->w_head, MOE_LAYOUT_PLAIN, w->b_head, T, n_h, w->n_out, MOE_BF16, pred_idx, (float *)(base + lay.prob),
+    return route_launch(cur, w->w_head, head_layout, w->b_head, T, n_h, w->n_out, MOE_BF16, pred_idx, (float *)(base + lay.prob),
                         logits_opt, base + lay.rws, st, "sru_predict/head");
 }

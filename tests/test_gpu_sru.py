@@ -31,6 +31,12 @@ def _compare(moe, s, what):
     assert (got[diff] == ref["idx2"][diff]).all()
     assert diff.mean() <= 0.02, f"{what}: {diff.mean():.3%} of predictions differ"
     print(f"{what}: max logit err {err:.2e} (scale {scale:.2f}), {int(diff.sum())} near-tie flips", flush=True)
+    if s["n_out"] in (128, 256):
+        # weights packed once by the caller: same kernels, same bits
+        wp = moe.SruWeights([to_dev(w) for w in s["w_cat"]], [to_dev(b) for b in s["b_f"]],
+                            [to_dev(b) for b in s["b_r"]], to_dev(s["w_head"]), to_dev(s["b_head"]), pack=True)
+        pred2, logits2 = moe.sru_predict(to_dev(s["emb"]), wp, want_logits=True)
+        assert torch.equal(pred, pred2) and torch.equal(logits, logits2)
     return got, ref
 
 
