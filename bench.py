@@ -25,6 +25,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
+# HBM bytes per launch (fetched + written) of the two FFN GEMM kernels, from two rocprofv3 --pmc
+# runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads
+# for a plain 1 GiB copy (fetch x1.9999, write x1.0000); figures and commands in
+# profiles/moe_layer_cfg2.md.  Counters cannot be read inside a normal run, so the value is
+# carried here and refreshed whenever those kernels change.
+PMC_TRAFFIC_BYTES = {"cfg2": {"ffn_gemm1": 626.15e6 + 15.12e6, "ffn_gemm2": 619.65e6 + 3.78e6}}
+
 
 def _to_dev(a):
     import torch
@@ -188,7 +195,8 @@ def main():
     dom = ("ffn_gemm1", g1, bytes_g1) if g1 >= g2 else ("ffn_gemm2", g2, bytes_g2)
     ach = dom[2] / (dom[1] * 1e-3) / 1e9
     roofline = dict(bound="hbm", kernel=dom[0], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=None,
+                    frac=round(ach / HBM_PEAK_GBS, 4),
+                    traffic=PMC_TRAFFIC_BYTES.get(a.workload, {}).get(dom[0]),
                     avg_ms=round(dom[1], 5), algorithmic_bytes=int(dom[2]),
                     ffn_gemm1_ms=round(g1, 5), ffn_gemm2_ms=round(g2, 5),
                     ffn_mfma_tflops=round(2 * flops / ((g1 + g2) * 1e-3) / 1e12, 2),

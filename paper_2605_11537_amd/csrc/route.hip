@@ -183,7 +183,7 @@ int route_launch(const void *x, const void *w_router, int w_layout, const float 
             if (rc != MOE_OK) return rc;
             wp = ws;
         }
-        const int mbk = T <= 8192 ? 1 : T <= 32768 ? 2 : 4;
+        const int mbk = T <= 8192 ? 1 : 2;
         int grid = ceil_div(T, 32 * mbk);
 #define MOE_ROUTE_LAUNCH(NB_, MB_)                                                                            \
     hipLaunchKernelGGL((route_mfma_kernel<NB_, MB_>), dim3(grid), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x, \
