@@ -15,11 +15,12 @@
 
 namespace moe {
 
-constexpr int FFN_BM = 64;    // rows per tile
+constexpr int FFN_BM = 64;    // rows per tile (fp32 path; short tile of the bf16 path)
+constexpr int FFN_BM_TALL = 128;  // bf16 path: a slot is cut into tiles of up to 128 rows
 constexpr int FFN_BN = 128;   // columns per workgroup (bf16 path)
-constexpr int FFN_BK = 128;   // k chunk of the bf16 path
-constexpr int FFN_GROUP = 16;            // row tiles per chunk of the grouped order
-constexpr int FFN_GROUP_MIN_ITEMS = 512; // below this many row tiles the weight stream binds: contiguous order
+constexpr int FFN_BK = 128;   // k chunk of the bf16 path, tiles of up to 64 rows
+constexpr int FFN_BK_TALL = 64;   // k chunk for tiles of 65..128 rows
+constexpr int FFN_GROUP = 8;             // row tiles per chunk of the grouped order
 
 struct __attribute__((aligned(16))) WorkItem {
     int expert, row_begin, row_end;
@@ -51,6 +52,9 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
 {
     __shared__ int wave_sums[16];
     __shared__ int total;
+    __shared__ int n_distinct;
+    if (threadIdx.x == 0) n_distinct = 0;
+    __syncthreads();
     int P = n_slots_p[0];
     if (P > max_slots) P = max_slots;
     int base = 0;
@@ -72,6 +76,8 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
                 reuse = r1 - r0 > tile_rows;
             }
             if (e < 0) cnt = 0;
+            // experts that own at least one tile (slots of an expert are adjacent)
+            if (cnt > 0 && (p == 0 || slot_expert[p - 1] != e)) atomicAdd(&n_distinct, 1);
         }
         int off = base + block_scan_excl_1024(cnt, wave_sums, &total);
         for (int i = 0; i < cnt; ++i) {
@@ -95,8 +101,10 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
     if (threadIdx.x == 0) {
         int n = base < max_items ? base : max_items;
         n_items[0] = n;
-        // many row tiles = long slots: chunked, column-tile-major order (see grouped_tile_of)
-        n_items[1] = n >= FFN_GROUP_MIN_ITEMS ? FFN_GROUP : 0;
+        // two or more row tiles per expert on average: the weights are re-read from cache by many
+        // tiles, so use the chunked, column-tile-major order (see grouped_tile_of); otherwise the
+        // weight stream binds, every tile costs the same, and contiguous ranges balance exactly
+        n_items[1] = (n_distinct > 0 && n >= 2 * n_distinct) ? FFN_GROUP : 0;
     }
 }
 
@@ -107,7 +115,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
     const bf16_t *__restrict__ Wp, int K, int N, int E, const WorkItem *__restrict__ items,
     const int32_t *__restrict__ n_items, int max_rows, bf16_t *__restrict__ C)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t lds[gemm_lds_elems<2, FFN_BK>()];
+    // Two tile heights share the kernel.  Up to 64 rows: 2 row blocks per wavefront, k chunks of
+    // 128 (the weight-streaming shape).  65..128 rows: 4 row blocks per wavefront, so a weight
+    // byte fetched from L2/HBM feeds twice the rows -- experts with several tiles are bound by
+    // cache bandwidth on their weights, not by HBM.
+    constexpr int LDC = FFN_BN + 8;
+    constexpr int S0 = gemm_lds_elems<2, FFN_BK>(), S1 = gemm_lds_elems<4, FFN_BK_TALL>(), S2 = FFN_BM_TALL * LDC;
+    __shared__ __attribute__((aligned(16))) bf16_t lds[(S0 > S1 ? S0 : S1) > S2 ? (S0 > S1 ? S0 : S1) : S2];
     const int n_nt = N / FFN_BN;
     int item, nt;
     if (!grouped_tile_of(blockIdx.x, n_items[0], n_nt, n_items[1], item, nt)) return;
@@ -116,33 +130,41 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
     const bf16_t *Bp = Wp + (size_t)it.expert * K * N;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int row_end = it.row_end < max_rows ? it.row_end : max_rows;
-    for (int r0 = it.row_begin; r0 < row_end; r0 += FFN_BM) {
-        const int nrows = row_end - r0 < FFN_BM ? row_end - r0 : FFN_BM;
-        f32x16_t acc[2][1];
-        zero_acc<2, 1>(acc);
+    for (int r0 = it.row_begin; r0 < row_end; r0 += FFN_BM_TALL) {
+        const int nrows = row_end - r0 < FFN_BM_TALL ? row_end - r0 : FFN_BM_TALL;
         const bf16_t *a0 = row_index ? A : A + (size_t)r0 * K;
         const int32_t *ri = row_index ? row_index + r0 : nullptr;
-        if (it.reuse)
-            gemm_tile_bf16<2, 1, FFN_BK, false>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc, ri, n_src_rows);
-        else
-            gemm_tile_bf16<2, 1, FFN_BK, true>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc, ri, n_src_rows);
+        f32x16_t acc[4][1];
+        zero_acc<4, 1>(acc);
+        if (nrows <= FFN_BM) {
+            f32x16_t(&acc2)[2][1] = reinterpret_cast<f32x16_t(&)[2][1]>(acc);
+            if (it.reuse)
+                gemm_tile_bf16<2, 1, FFN_BK, false>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc2, ri, n_src_rows);
+            else
+                gemm_tile_bf16<2, 1, FFN_BK, true>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc2, ri, n_src_rows);
+        } else {
+            if (it.reuse)
+                gemm_tile_bf16<4, 1, FFN_BK_TALL, false>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc, ri, n_src_rows);
+            else
+                gemm_tile_bf16<4, 1, FFN_BK_TALL, true>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc, ri, n_src_rows);
+        }
         // Epilogue through LDS: an accumulator lane holds single columns of 16 different rows,
-        // and 2-byte stores that cover a quarter of a cache line each cost more HBM time than
-        // the whole weight stream of a small tile.  The tile is transposed in LDS (the A buffers
-        // are free after the last barrier of the product) and leaves as 16-byte stores, 16
-        // consecutive lanes writing the 256 contiguous bytes of one row.
-        constexpr int LDC = FFN_BN + 8;
+        // and 2-byte stores that cover a quarter of a cache line each are slow.  The tile is
+        // transposed in LDS (the A buffers are free after the last barrier of the product) and
+        // leaves as 16-byte stores, 16 consecutive lanes writing the 256 contiguous bytes of a row.
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int mb = 0; mb < 4; ++mb)
+            if (mb * 32 < nrows) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float val = acc[mb][0][v];
-                if (RELU) val = val > 0.f ? val : 0.f;
-                lds[(mb * 32 + acc_row(v, lane)) * LDC + w * 32 + (lane & 31)] = f32_to_bf16(val);
+                for (int v = 0; v < 16; ++v) {
+                    float val = acc[mb][0][v];
+                    if (RELU) val = val > 0.f ? val : 0.f;
+                    lds[(mb * 32 + acc_row(v, lane)) * LDC + w * 32 + (lane & 31)] = f32_to_bf16(val);
+                }
             }
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < FFN_BM * (FFN_BN / 8) / GEMM_THREADS; ++i) {
+        for (int i = 0; i < FFN_BM_TALL * (FFN_BN / 8) / GEMM_THREADS; ++i) {
             int p = threadIdx.x + i * GEMM_THREADS;
             int r = p / (FFN_BN / 8), c8 = p % (FFN_BN / 8);
             if (r < nrows)
@@ -314,7 +336,7 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
     p += align_up((size_t)max_items * sizeof(WorkItem), 256);
     int32_t *n_items = (int32_t *)p;
 
-    const int tile_rows = FFN_BM;
+    const int tile_rows = dtype == MOE_BF16 ? FFN_BM_TALL : FFN_BM;
     hipLaunchKernelGGL(ffn_worklist_kernel, dim3(1), dim3(1024), 0, st, slot_offset, slot_expert, n_slots, max_slots,
                        max_items, schedule, tile_rows, items, n_items);
     MOE_CHECK_LAUNCH("moe_expert_ffn/worklist");

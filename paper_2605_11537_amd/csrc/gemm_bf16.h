@@ -136,6 +136,9 @@ __device__ __forceinline__ void gemm_tile_bf16(const bf16_t *__restrict__ A, int
             load_a(kc + 1);
             load_b(kc + 1, nxt);
         }
+        // keep the prefetch where it is: left alone, the scheduler sinks these loads below the
+        // matrix instructions to save registers, and every chunk then waits a full memory round trip
+        __builtin_amdgcn_sched_barrier(0);
         compute(kc, cur);
         if (more) store_a((kc + 1) & 1);
         __syncthreads();
