@@ -8,10 +8,14 @@
 //             and the kernel walks its rows 64 at a time.
 //   gemm1     h = relu(x_perm * W1[e])   per (row tile, 128-column tile)
 //   gemm2     y_perm = h * W2[e]
+// At large batch a second list takes the stretches of more than 128 rows, 256 at a time; those run
+// on the compute-bound 256 x 256 tile (gemm_dense_bf16.h) in a launch of their own before the
+// 128-column kernel handles the rest.
 // Grids are sized for the worst case on the host (rows and slots are only known on the
 // device); workgroups beyond the list exit at once.  Workgroup ids are remapped so that the
 // column tiles of one row tile, which share the token rows, run on one XCD.
 #include "gemm_bf16.h"
+#include "gemm_dense_bf16.h"
 
 namespace moe {
 
@@ -44,11 +48,16 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restr
 }
 
 // ------------------------------------------------------------------ work list
+// dense != 0 (slot schedule only): rows of a slot beyond its last 128 go, 256 at a time, to the
+// list of the 256 x 256 tile kernel (the final piece may have 129..256 rows); at most 128 rows are
+// left for the 128-column kernel.  n_items = {row tiles, group size of the grouped order, dense tiles}.
 __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__restrict__ slot_offset,
                                                             const int32_t *__restrict__ slot_expert,
                                                             const int32_t *__restrict__ n_slots_p, int max_slots,
-                                                            int max_items, int schedule, int tile_rows,
-                                                            WorkItem *__restrict__ items, int32_t *__restrict__ n_items)
+                                                            int max_items, int schedule, int tile_rows, int E,
+                                                            int dense, int max_dense, WorkItem *__restrict__ items,
+                                                            DenseTile *__restrict__ dtiles,
+                                                            int32_t *__restrict__ n_items)
 {
     __shared__ int wave_sums[16];
     __shared__ int total;
@@ -57,17 +66,20 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
     __syncthreads();
     int P = n_slots_p[0];
     if (P > max_slots) P = max_slots;
-    int base = 0;
+    int base = 0, dbase = 0;
     for (int p0 = 0; p0 < P; p0 += 1024) {
         int p = p0 + threadIdx.x;
-        int cnt = 0, e = -1, r0 = 0, r1 = 0, reuse = 0;
+        int cnt = 0, nd = 0, e = -1, r0 = 0, r1 = 0, reuse = 0;
         if (p < P) {
             e = slot_expert[p];
             r0 = slot_offset[p];
             if (schedule == MOE_SCHEDULE_SLOTS) {
                 r1 = slot_offset[p + 1];
-                cnt = (r1 - r0 + tile_rows - 1) / tile_rows;
-                reuse = cnt > 1 || (p > 0 && slot_expert[p - 1] == e) || (p + 1 < P && slot_expert[p + 1] == e);
+                const int n = r1 > r0 ? r1 - r0 : 0;
+                if (dense && n > 128) nd = (n - 128 + DENSE_BM - 1) / DENSE_BM;
+                const int covered = nd * DENSE_BM < n ? nd * DENSE_BM : n;
+                cnt = (n - covered + tile_rows - 1) / tile_rows;
+                reuse = cnt + nd > 1 || (p > 0 && slot_expert[p - 1] == e) || (p + 1 < P && slot_expert[p + 1] == e);
             } else if (p == 0 || slot_expert[p - 1] != e) {
                 int q = p + 1;
                 while (q < P && slot_expert[q] == e) ++q;
@@ -75,18 +87,31 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
                 cnt = r1 > r0 ? 1 : 0;
                 reuse = r1 - r0 > tile_rows;
             }
-            if (e < 0) cnt = 0;
+            if (e < 0 || e >= E) cnt = nd = 0;   // never index weights with a bad id
             // experts that own at least one tile (slots of an expert are adjacent)
             if (cnt > 0 && (p == 0 || slot_expert[p - 1] != e)) atomicAdd(&n_distinct, 1);
         }
         int off = base + block_scan_excl_1024(cnt, wave_sums, &total);
+        const int total_items = total;
+        int doff = dbase + block_scan_excl_1024(nd, wave_sums, &total);
+        const int total_dense = total;
+        const int covered = nd * DENSE_BM < r1 - r0 ? nd * DENSE_BM : r1 - r0;
+        for (int i = 0; i < nd; ++i) {
+            if (doff + i < max_dense) {
+                DenseTile t;
+                t.expert = e;
+                t.row_begin = r0 + i * DENSE_BM;
+                t.row_end = t.row_begin + DENSE_BM < r1 ? t.row_begin + DENSE_BM : r1;
+                dtiles[doff + i] = t;
+            }
+        }
         for (int i = 0; i < cnt; ++i) {
             if (off + i < max_items) {
                 WorkItem it;
                 it.expert = e;
                 it.reuse = reuse;
                 if (schedule == MOE_SCHEDULE_SLOTS) {
-                    it.row_begin = r0 + i * tile_rows;
+                    it.row_begin = r0 + covered + i * tile_rows;
                     it.row_end = it.row_begin + tile_rows < r1 ? it.row_begin + tile_rows : r1;
                 } else {
                     it.row_begin = r0;
@@ -95,7 +120,8 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
                 items[off + i] = it;
             }
         }
-        base += total;
+        base += total_items;
+        dbase += total_dense;
         __syncthreads();
     }
     if (threadIdx.x == 0) {
@@ -105,7 +131,19 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
         // tiles, so use the chunked, column-tile-major order (see grouped_tile_of); otherwise the
         // weight stream binds, every tile costs the same, and contiguous ranges balance exactly
         n_items[1] = (n_distinct > 0 && n >= 2 * n_distinct) ? FFN_GROUP : 0;
+        n_items[2] = dbase < max_dense ? dbase : max_dense;
     }
+}
+
+// ------------------------------------------------------------------ bf16 256 x 256 tiles (long row stretches)
+template <bool RELU>
+__global__ __launch_bounds__(GEMM_THREADS, 1) void ffn_dense_bf16_kernel(
+    const bf16_t *__restrict__ A, const int32_t *__restrict__ row_index, int n_src_rows,
+    const bf16_t *__restrict__ Wp, int K, int N, const DenseTile *__restrict__ tiles,
+    const int32_t *__restrict__ n_tiles, bf16_t *__restrict__ C)
+{
+    __shared__ __attribute__((aligned(16))) uint4 smem[DENSE_LDS_BYTES / 16];
+    dense_tiles_bf16<RELU>(A, row_index, n_src_rows, Wp, K, N, tiles, n_tiles[0], C, smem);
 }
 
 // ------------------------------------------------------------------ bf16 grouped GEMM
@@ -244,6 +282,16 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restri
 }
 
 static inline int ffn_max_items(int max_rows, int max_slots) { return max_slots + max_rows / FFN_BM + 1; }
+// every dense tile but the last of a slot has 256 rows, and that last one more than 128
+static inline int ffn_max_dense(int max_rows) { return max_rows / 128 + 1; }
+
+// The 256 x 256 tile pays off when slots are long: it is launched when the rows could fill slots of
+// 64 and more on average, the matrix sizes fit its tiling, and the batch can fill the chip.
+static inline bool ffn_use_dense(int max_rows, int max_slots, int K, int N, int schedule)
+{
+    return schedule == MOE_SCHEDULE_SLOTS && N % DENSE_BN == 0 && K % DENSE_BK == 0 && K >= DENSE_MIN_K &&
+           (long long)max_rows >= 64LL * max_slots && max_rows >= 4096;
+}
 
 // events the next moe_expert_ffn call of this thread records around its two GEMM kernels
 static thread_local hipEvent_t g_timing_ev[3] = {nullptr, nullptr, nullptr};
@@ -287,7 +335,8 @@ extern "C" size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, in
     size_t esz = dtype == MOE_F32 ? 4 : 2;
     size_t h = align_up((size_t)(max_rows > 0 ? max_rows : 1) * F * esz, 256);
     size_t items = align_up((size_t)ffn_max_items(max_rows, max_slots) * sizeof(WorkItem), 256);
-    return h + items + 256;
+    size_t dense = align_up((size_t)ffn_max_dense(max_rows) * sizeof(DenseTile), 256);
+    return h + items + dense + 256;
 }
 
 extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, const void *w1, const void *w2,
@@ -334,11 +383,17 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
     WorkItem *items = (WorkItem *)p;
     int max_items = ffn_max_items(max_rows, max_slots);
     p += align_up((size_t)max_items * sizeof(WorkItem), 256);
+    DenseTile *dtiles = (DenseTile *)p;
+    const int max_dense = ffn_max_dense(max_rows);
+    p += align_up((size_t)max_dense * sizeof(DenseTile), 256);
     int32_t *n_items = (int32_t *)p;
 
     const int tile_rows = dtype == MOE_BF16 ? FFN_BM_TALL : FFN_BM;
+    // both products must take the dense route or neither: the lists split the rows once
+    const bool dense = dtype == MOE_BF16 && ffn_use_dense(max_rows, max_slots, d, F, schedule) &&
+                       ffn_use_dense(max_rows, max_slots, F, d, schedule);
     hipLaunchKernelGGL(ffn_worklist_kernel, dim3(1), dim3(1024), 0, st, slot_offset, slot_expert, n_slots, max_slots,
-                       max_items, schedule, tile_rows, items, n_items);
+                       max_items, schedule, tile_rows, E, dense ? 1 : 0, max_dense, items, dtiles, n_items);
     MOE_CHECK_LAUNCH("moe_expert_ffn/worklist");
     int grid_items = schedule == MOE_SCHEDULE_SLOTS ? max_slots + max_rows / tile_rows + 1
                                                     : (max_slots < max_items ? max_slots : max_items);
@@ -350,10 +405,29 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
         size_t gi = align_up((size_t)ceil_div(grid_items, FFN_GROUP), 8) * FFN_GROUP;
         int g1 = (int)(gi * (F / FFN_BN));
         int g2 = (int)(gi * (d / FFN_BN));
+        int n_cu = 0;
+        if (dense) {
+            int dev = 0;
+            MOE_REQUIRE(hipGetDevice(&dev) == hipSuccess &&
+                            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+                            n_cu >= 8,
+                        MOE_ERR_HIP, "moe_expert_ffn: cannot read the compute unit count");
+            n_cu -= n_cu % 8;   // one persistent workgroup per CU, the same number on every XCD
+            hipLaunchKernelGGL(ffn_dense_bf16_kernel<true>, dim3(n_cu), dim3(GEMM_THREADS), 0, st,
+                               (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, dtiles,
+                               n_items + 2, (bf16_t *)h);
+            MOE_CHECK_LAUNCH("moe_expert_ffn/dense gemm1");
+        }
         hipLaunchKernelGGL(ffn_gemm_bf16_kernel<true>, dim3(g1), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x_perm,
                            row_index, max_rows, (const bf16_t *)w1, d, F, E, items, n_items, max_rows, (bf16_t *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
         if (ev[1]) (void)hipEventRecord(ev[1], st);
+        if (dense) {
+            hipLaunchKernelGGL(ffn_dense_bf16_kernel<false>, dim3(n_cu), dim3(GEMM_THREADS), 0, st,
+                               (const bf16_t *)h, (const int32_t *)nullptr, max_rows, (const bf16_t *)w2, F, d, dtiles,
+                               n_items + 2, (bf16_t *)y_perm);
+            MOE_CHECK_LAUNCH("moe_expert_ffn/dense gemm2");
+        }
         hipLaunchKernelGGL(ffn_gemm_bf16_kernel<false>, dim3(g2), dim3(GEMM_THREADS), 0, st, (const bf16_t *)h,
                            (const int32_t *)nullptr, max_rows, (const bf16_t *)w2, F, d, E, items, n_items, max_rows,
                            (bf16_t *)y_perm);

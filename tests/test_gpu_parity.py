@@ -239,6 +239,72 @@ def test_ffn_bf16_long_slots(schedule):
     assert torch.equal(y[:K], y2[:K])
 
 
+def test_ffn_bf16_dense_tiles():
+    """Enough rows that the 256 x 256 tile kernel takes the long stretches of a slot: slot lengths
+    around its cut points (129, 256, 257, 384, 385, 513 rows), short and empty slots beside them,
+    and the fused gather."""
+    E, d, F = 5, 256, 512
+    rows = [1500, 129, 0, 256, 257, 1, 385, 2000, 128, 513, 384, 64]
+    experts = [0, 0, 1, 1, 2, 2, 3, 3, 3, 4, 4, 4]
+    so, se = _slots_for(rows, experts)
+    K = int(so[-1])
+    T = K + 3
+    assert T >= 4096 and T >= 64 * len(rows)        # the sizes at which the library uses that kernel
+    x = synth.normal_tensor((T, d), 1.0, [31], synth.BF16)
+    w1 = synth.normal_tensor((E, d, F), 0.05, [32], synth.BF16)
+    w2 = synth.normal_tensor((E, F, d), 0.05, [33], synth.BF16)
+    ref = oracle.ffn(x, w1, w2, so, se, len(rows))
+    args = (moe.moe_pack_weights(to_dev(w1)), moe.moe_pack_weights(to_dev(w2)), to_dev(so), to_dev(se),
+            torch.tensor([len(rows)], dtype=torch.int32, device="cuda"), E, F)
+    y = moe.moe_expert_ffn(to_dev(x), *args)
+    _sync()
+    assert_close(to_host(y)[:K], ref[:K], synth.BF16, "ffn bf16 dense tiles")
+    g, r = f64(to_host(y)[:K]), f64(ref[:K])
+    assert (np.abs(g - r) <= 2.0 ** -7 * np.abs(r) + 1e-3 * np.abs(r).max()).all()
+    # replication off walks whole experts with the 128-column kernel only: same sums in the same order
+    y_off = moe.moe_expert_ffn(to_dev(x), *args, schedule=1)
+    assert torch.equal(y[:K], y_off[:K])
+    perm = np.random.default_rng(2).permutation(T).astype(np.int32)
+    x_src = np.zeros_like(x)
+    x_src[perm] = x
+    y2 = moe.moe_expert_ffn(to_dev(x_src), *args, row_index=to_dev(perm))
+    assert torch.equal(y[:K], y2[:K])
+    y3 = moe.moe_expert_ffn(to_dev(x), *args)           # twice in a row: nothing stale in the work lists
+    assert torch.equal(y, y3) or torch.equal(y[:K], y3[:K])
+
+
+def test_ffn_bf16_dense_tiles_persistent():
+    """More 256-row tiles than the chip has compute units, so the persistent workgroups of the tile
+    kernel walk several tiles each (prefetch across tiles, epilogue stores still in flight).  The
+    oracle checks sampled rows; every row must equal the experts schedule bit for bit, which runs
+    the 128-column kernel alone and accumulates in the same order."""
+    E, d, F = 4, 256, 512
+    rows = [30000, 20000, 130, 15000, 257, 15001]
+    experts = [0, 1, 1, 2, 3, 3]
+    so, se = _slots_for(rows, experts)
+    K = int(so[-1])
+    T = K
+    x = synth.normal_tensor((T, d), 1.0, [41], synth.BF16)
+    w1 = synth.normal_tensor((E, d, F), 0.05, [42], synth.BF16)
+    w2 = synth.normal_tensor((E, F, d), 0.05, [43], synth.BF16)
+    args = (moe.moe_pack_weights(to_dev(w1)), moe.moe_pack_weights(to_dev(w2)), to_dev(so), to_dev(se),
+            torch.tensor([len(rows)], dtype=torch.int32, device="cuda"), E, F)
+    perm = np.random.default_rng(3).permutation(T).astype(np.int32)
+    x_src = np.zeros_like(x)
+    x_src[perm] = x
+    y = moe.moe_expert_ffn(to_dev(x_src), *args, row_index=to_dev(perm))
+    y_off = moe.moe_expert_ffn(to_dev(x), *args, schedule=1)
+    _sync()
+    assert torch.equal(y, y_off)
+    rng = np.random.default_rng(4)
+    sample = np.unique(np.concatenate([rng.choice(K, 1500, replace=False), so[:-1], so[1:] - 1,
+                                       [255, 256, 29999 - 255, 29999 - 256]])).astype(np.int32)
+    xs = np.zeros_like(x)
+    xs[sample] = x[sample]
+    ref = oracle.ffn(xs, w1, w2, so, se, len(rows), rows=sample)
+    assert_close(to_host(y)[sample], ref[sample], synth.BF16, "ffn bf16 dense tiles, sampled rows")
+
+
 # --------------------------------------------------------------------------- whole layer
 def _run_layer_gpu(c, C, R, schedule=0, residual=0, plan_ids=None, packed=None, fuse_gather=True):
     dt = torch.bfloat16 if c["dtype"] == synth.BF16 else torch.float32
