@@ -25,6 +25,7 @@ constexpr int FFN_BN = 128;   // columns per workgroup (bf16 path)
 constexpr int FFN_BK = 128;   // k chunk of the bf16 path, tiles of up to 64 rows
 constexpr int FFN_BK_TALL = 64;   // k chunk for tiles of 65..128 rows
 constexpr int FFN_GROUP = 8;             // row tiles per chunk of the grouped order
+constexpr int FFN_DENSE_MIN_ROWS = 64;   // a slot's last piece goes to the 256 x 256 tile kernel if longer than this
 
 struct __attribute__((aligned(16))) WorkItem {
     int expert, row_begin, row_end;
@@ -48,9 +49,10 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restr
 }
 
 // ------------------------------------------------------------------ work list
-// dense != 0 (slot schedule only): rows of a slot beyond its last 128 go, 256 at a time, to the
-// list of the 256 x 256 tile kernel (the final piece may have 129..256 rows); at most 128 rows are
-// left for the 128-column kernel.  n_items = {row tiles, group size of the grouped order, dense tiles}.
+// dense != 0 (slot schedule only): a slot's rows go, 256 at a time, to the list of the 256 x 256 tile
+// kernel (it skips the row blocks a shorter last piece does not have); only a last piece of at most
+// 64 rows, the weight-streaming case, stays with the 128-column kernel.
+// n_items = {row tiles, group size of the grouped order, dense tiles}.
 __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__restrict__ slot_offset,
                                                             const int32_t *__restrict__ slot_expert,
                                                             const int32_t *__restrict__ n_slots_p, int max_slots,
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
             if (schedule == MOE_SCHEDULE_SLOTS) {
                 r1 = slot_offset[p + 1];
                 const int n = r1 > r0 ? r1 - r0 : 0;
-                if (dense && n > 128) nd = (n - 128 + DENSE_BM - 1) / DENSE_BM;
+                if (dense) nd = n / DENSE_BM + (n % DENSE_BM > FFN_DENSE_MIN_ROWS ? 1 : 0);
                 const int covered = nd * DENSE_BM < n ? nd * DENSE_BM : n;
                 cnt = (n - covered + tile_rows - 1) / tile_rows;
                 reuse = cnt + nd > 1 || (p > 0 && slot_expert[p - 1] == e) || (p + 1 < P && slot_expert[p + 1] == e);
@@ -147,18 +149,21 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void ffn_dense_bf16_kernel(
 }
 
 // ------------------------------------------------------------------ bf16 grouped GEMM
-template <bool RELU>
-__global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
+// Two tile heights.  Up to 64 rows: 2 row blocks per wavefront, k chunks of 128 -- the
+// weight-streaming shape.  65..128 rows (TALL builds only): 4 row blocks per wavefront, so a weight
+// byte fetched from L2/HBM feeds twice the rows.  The build without the tall tile walks a work item
+// 64 rows at a time.  (Three or four workgroups per CU instead of two, tried with a k chunk of 64 to
+// fit the registers, changed the HBM-bound launches by under 1%: two it stays.)
+template <bool RELU, bool TALL>
+__global__ __launch_bounds__(GEMM_THREADS, 2) void ffn_gemm_bf16_kernel(
     const bf16_t *__restrict__ A, const int32_t *__restrict__ row_index, int n_src_rows,
     const bf16_t *__restrict__ Wp, int K, int N, int E, const WorkItem *__restrict__ items,
     const int32_t *__restrict__ n_items, int max_rows, bf16_t *__restrict__ C)
 {
-    // Two tile heights share the kernel.  Up to 64 rows: 2 row blocks per wavefront, k chunks of
-    // 128 (the weight-streaming shape).  65..128 rows: 4 row blocks per wavefront, so a weight
-    // byte fetched from L2/HBM feeds twice the rows -- experts with several tiles are bound by
-    // cache bandwidth on their weights, not by HBM.
+    constexpr int TM = TALL ? FFN_BM_TALL : FFN_BM;          // rows per pass over a work item
+    constexpr int MBT = TM / 32;
     constexpr int LDC = FFN_BN + 8;
-    constexpr int S0 = gemm_lds_elems<2, FFN_BK>(), S1 = gemm_lds_elems<4, FFN_BK_TALL>(), S2 = FFN_BM_TALL * LDC;
+    constexpr int S0 = gemm_lds_elems<2, FFN_BK>(), S1 = TALL ? gemm_lds_elems<4, FFN_BK_TALL>() : 0, S2 = TM * LDC;
     __shared__ __attribute__((aligned(16))) bf16_t lds[(S0 > S1 ? S0 : S1) > S2 ? (S0 > S1 ? S0 : S1) : S2];
     const int n_nt = N / FFN_BN;
     int item, nt;
@@ -168,19 +173,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
     const bf16_t *Bp = Wp + (size_t)it.expert * K * N;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int row_end = it.row_end < max_rows ? it.row_end : max_rows;
-    for (int r0 = it.row_begin; r0 < row_end; r0 += FFN_BM_TALL) {
-        const int nrows = row_end - r0 < FFN_BM_TALL ? row_end - r0 : FFN_BM_TALL;
+    for (int r0 = it.row_begin; r0 < row_end; r0 += TM) {
+        const int nrows = row_end - r0 < TM ? row_end - r0 : TM;
         const bf16_t *a0 = row_index ? A : A + (size_t)r0 * K;
         const int32_t *ri = row_index ? row_index + r0 : nullptr;
-        f32x16_t acc[4][1];
-        zero_acc<4, 1>(acc);
-        if (nrows <= FFN_BM) {
+        f32x16_t acc[MBT][1];
+        zero_acc<MBT, 1>(acc);
+        if (!TALL || nrows <= FFN_BM) {
             f32x16_t(&acc2)[2][1] = reinterpret_cast<f32x16_t(&)[2][1]>(acc);
             if (it.reuse)
                 gemm_tile_bf16<2, 1, FFN_BK, false>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc2, ri, n_src_rows);
             else
                 gemm_tile_bf16<2, 1, FFN_BK, true>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc2, ri, n_src_rows);
-        } else {
+        } else if constexpr (TALL) {
             if (it.reuse)
                 gemm_tile_bf16<4, 1, FFN_BK_TALL, false>(a0, K, nrows, Bp, nt * FFN_BN, K, lds, acc, ri, n_src_rows);
             else
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
         // transposed in LDS (the A buffers are free after the last barrier of the product) and
         // leaves as 16-byte stores, 16 consecutive lanes writing the 256 contiguous bytes of a row.
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
+        for (int mb = 0; mb < MBT; ++mb)
             if (mb * 32 < nrows) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -202,7 +207,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void ffn_gemm_bf16_kernel(
             }
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < FFN_BM_TALL * (FFN_BN / 8) / GEMM_THREADS; ++i) {
+        for (int i = 0; i < TM * (FFN_BN / 8) / GEMM_THREADS; ++i) {
             int p = threadIdx.x + i * GEMM_THREADS;
             int r = p / (FFN_BN / 8), c8 = p % (FFN_BN / 8);
             if (r < nrows)
@@ -282,8 +287,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restri
 }
 
 static inline int ffn_max_items(int max_rows, int max_slots) { return max_slots + max_rows / FFN_BM + 1; }
-// every dense tile but the last of a slot has 256 rows, and that last one more than 128
-static inline int ffn_max_dense(int max_rows) { return max_rows / 128 + 1; }
+// every dense tile but the last of a slot has 256 rows, and that last one more than 64
+static inline int ffn_max_dense(int max_rows) { return max_rows / 64 + 1; }
 
 // The 256 x 256 tile pays off when slots are long: it is launched when the rows could fill slots of
 // 64 and more on average, the matrix sizes fit its tiling, and the batch can fill the chip.
@@ -388,10 +393,14 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
     p += align_up((size_t)max_dense * sizeof(DenseTile), 256);
     int32_t *n_items = (int32_t *)p;
 
-    const int tile_rows = dtype == MOE_BF16 ? FFN_BM_TALL : FFN_BM;
     // both products must take the dense route or neither: the lists split the rows once
     const bool dense = dtype == MOE_BF16 && ffn_use_dense(max_rows, max_slots, d, F, schedule) &&
                        ffn_use_dense(max_rows, max_slots, F, d, schedule);
+    // The 128-row tile of the 128-column kernel is for long slots the dense kernel does not take (small
+    // batches, shapes outside its tiling).  With the dense kernel on, or with slots that can hold 64 rows
+    // on average at most, work items are cut 64 rows high and the leaner build of the kernel runs.
+    const bool tall = dtype == MOE_BF16 && !dense && (long long)max_rows > 64LL * max_slots;
+    const int tile_rows = tall ? FFN_BM_TALL : FFN_BM;
     hipLaunchKernelGGL(ffn_worklist_kernel, dim3(1), dim3(1024), 0, st, slot_offset, slot_expert, n_slots, max_slots,
                        max_items, schedule, tile_rows, E, dense ? 1 : 0, max_dense, items, dtiles, n_items);
     MOE_CHECK_LAUNCH("moe_expert_ffn/worklist");
@@ -418,8 +427,14 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
                                n_items + 2, (bf16_t *)h);
             MOE_CHECK_LAUNCH("moe_expert_ffn/dense gemm1");
         }
-        hipLaunchKernelGGL(ffn_gemm_bf16_kernel<true>, dim3(g1), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x_perm,
-                           row_index, max_rows, (const bf16_t *)w1, d, F, E, items, n_items, max_rows, (bf16_t *)h);
+        if (tall)
+            hipLaunchKernelGGL((ffn_gemm_bf16_kernel<true, true>), dim3(g1), dim3(GEMM_THREADS), 0, st,
+                               (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, E, items,
+                               n_items, max_rows, (bf16_t *)h);
+        else
+            hipLaunchKernelGGL((ffn_gemm_bf16_kernel<true, false>), dim3(g1), dim3(GEMM_THREADS), 0,
+                               st, (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, E, items,
+                               n_items, max_rows, (bf16_t *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
         if (ev[1]) (void)hipEventRecord(ev[1], st);
         if (dense) {
@@ -428,9 +443,14 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
                                n_items + 2, (bf16_t *)y_perm);
             MOE_CHECK_LAUNCH("moe_expert_ffn/dense gemm2");
         }
-        hipLaunchKernelGGL(ffn_gemm_bf16_kernel<false>, dim3(g2), dim3(GEMM_THREADS), 0, st, (const bf16_t *)h,
-                           (const int32_t *)nullptr, max_rows, (const bf16_t *)w2, F, d, E, items, n_items, max_rows,
-                           (bf16_t *)y_perm);
+        if (tall)
+            hipLaunchKernelGGL((ffn_gemm_bf16_kernel<false, true>), dim3(g2), dim3(GEMM_THREADS), 0, st,
+                               (const bf16_t *)h, (const int32_t *)nullptr, max_rows, (const bf16_t *)w2, F, d, E,
+                               items, n_items, max_rows, (bf16_t *)y_perm);
+        else
+            hipLaunchKernelGGL((ffn_gemm_bf16_kernel<false, false>), dim3(g2), dim3(GEMM_THREADS), 0,
+                               st, (const bf16_t *)h, (const int32_t *)nullptr, max_rows, (const bf16_t *)w2, F, d, E,
+                               items, n_items, max_rows, (bf16_t *)y_perm);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm2");
     } else {
         int g1 = grid_items * (F / 64), g2 = grid_items * (d / 64);

@@ -25,14 +25,15 @@
 // vector memory operations complete in issue order, so "at most P outstanding" means every load
 // older than the newest P has landed.
 //
-// The kernel is persistent: workgroup b of XCD x walks tiles x's contiguous share, round robin with
-// the other workgroups of that XCD.  The loads of the next tile's first stages are issued during
+// The kernel is persistent: the row ranges are dealt to the XCDs in turn, and the workgroups of an XCD
+// walk its tiles round robin.  The loads of the next tile's first stages are issued during
 // the last stages of the current one, and each wavefront converts and stores its own 128 x 128 part
 // through a private LDS strip, so the epilogue has no workgroup barrier.  The matrix instruction is
 // fed (weights, tokens), i.e. it computes the transposed block: a lane then holds 4 consecutive
 // output columns of one token, which pack into one 8-byte LDS write.
 #pragma once
 #include "gemm_bf16.h"
+#include <type_traits>
 
 namespace moe {
 
@@ -64,6 +65,15 @@ typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
                  : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]))
 #define MOE_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n)&15) | (((n) >> 4) << 14))
 #define MOE_SB() __builtin_amdgcn_sched_barrier(0)
+// wait until at most base + extra operations are outstanding; extra is 0, 8, 16, 24 or 32 (the wait takes an immediate)
+#define MOE_VMCNT_PLUS(base, extra)                                                                                  \
+    do {                                                                                                             \
+        if ((extra) == 0) MOE_VMCNT(base);                                                                           \
+        else if ((extra) == 8) MOE_VMCNT((base) + 8);                                                                \
+        else if ((extra) == 16) MOE_VMCNT((base) + 16);                                                              \
+        else if ((extra) == 24) MOE_VMCNT((base) + 24);                                                              \
+        else MOE_VMCNT((base) + 32);                                                                                 \
+    } while (0)
 
 // A: token rows (row-major, K contiguous); row_idx (optional): tile row r reads A[row_idx[row_begin + r]].
 // Wp: packed weights of all experts (K x N each).  tiles[0..n_tiles): row ranges of at most 256 rows,
@@ -77,12 +87,15 @@ __device__ __forceinline__ void dense_tiles_bf16(const bf16_t *__restrict__ A, c
     constexpr int NS = DENSE_NS, STAGE = DENSE_STAGE, BK = DENSE_BK, LDE = DENSE_LDE;
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = w >> 1, wn = w & 1;
-    const int n_nt = N / DENSE_BN, n_tiles = n_items * n_nt;
+    const int n_nt = N / DENSE_BN;
     const int nk = K / BK, KG = K >> 3;
-    // this workgroup's tiles: XCD x owns a contiguous range, its workgroups take them round robin
+    // This workgroup's tiles.  Row ranges are dealt to the 8 XCDs in turn (range i to XCD i % 8, with all
+    // its column tiles, which share the token rows in that L2); tiles differ in cost by their row count
+    // and long runs of one kind follow each other in the list, so dealing mixes them evenly.  The
+    // workgroups of an XCD take its tiles round robin.
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
-    const int t_begin = (int)((long long)n_tiles * xcd / 8), t_end = (int)((long long)n_tiles * (xcd + 1) / 8);
-    int lin = t_begin + local;
+    const int t_end = n_items > xcd ? ((n_items - xcd + 7) >> 3) * n_nt : 0;
+    int lin = local;                   // position in this XCD's sequence of tiles
     if (lin >= t_end) return;
 
     const unsigned lds0 = (unsigned)(unsigned long)(lds_void_t *)smem;
@@ -91,7 +104,7 @@ __device__ __forceinline__ void dense_tiles_bf16(const bf16_t *__restrict__ A, c
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
         const int kg = 2 * ks + (lane >> 5);
-        a_addr[ks] = lds0 + 16u * ((wm * 8 + ((lane & 31) >> 4)) * 64 + r16 * 4 + (kg ^ (r16 >> 2) ^ (r16 & 3)));
+        a_addr[ks] = lds0 + 16u * ((wm * 2 + ((lane & 31) >> 4)) * 64 + r16 * 4 + (kg ^ (r16 >> 2) ^ (r16 & 3)));
         b_addr[ks] = lds0 + 16u * ((16 + wn * 8 + ks) * 64 + lane);
     }
     // what this lane loads: token row (lane >> 2) of units 4w..4w+3, k-group by the swizzle; weight units 4w..4w+3
@@ -101,8 +114,9 @@ __device__ __forceinline__ void dense_tiles_bf16(const bf16_t *__restrict__ A, c
     const uint4 *b_src[4];
     int row0, nrows, nt;
     auto tile_rows = [&](int t, int &item, int &r0, int &n, int &ntile) {
-        item = t / n_nt;
-        ntile = t - item * n_nt;
+        const int q = t / n_nt;
+        ntile = t - q * n_nt;
+        item = q * 8 + xcd;
         const DenseTile tl = tiles[item];
         r0 = tl.row_begin;
         n = tl.row_end - tl.row_begin;
@@ -146,44 +160,52 @@ __device__ __forceinline__ void dense_tiles_bf16(const bf16_t *__restrict__ A, c
         set_sources(expert, src_row);
     }
     int buf = 0;                       // ring position of the current tile's stage 0
-    bool first = true;
+    int prev_stores = 0;               // stores of the previous tile's epilogue, younger than this tile's first loads
 #pragma unroll
     for (int s = 0; s < NS; ++s) issue(s, s);
 
     u32x4_t fx[8], fy[8];              // fragments of the two 16-deep steps: [0..3] token row blocks, [4..7] weight strips
+#pragma unroll
+    for (int i = 0; i < 8; ++i) fx[i] = fy[i] = (u32x4_t){0u, 0u, 0u, 0u};   // blocks a wavefront does not own are never read
 #define MOE_MF(f, mb, nb)                                                                                            \
+    if (mb < MYB)                                                                                                    \
     acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f[4 + nb]),                   \
                                                           __builtin_bit_cast(bf16x8_t, f[mb]), acc[mb][nb], 0, 0, 0)
     while (true) {
-        f32x16_t acc[4][4];
-        zero_acc<4, 4>(acc);
         const int next = lin + per_xcd;
         const bool has_next = next < t_end;
         int n_item, n_row0 = 0, n_nrows = 1, n_nt_ = 0, n_expert = 0;
         if (has_next) n_expert = tile_rows(next, n_item, n_row0, n_nrows, n_nt_);
+        const int cur_row0 = row0, cur_nrows = nrows, cur_nt = nt;
+        // Row blocks of 32 are dealt to the two wavefront rows in turn (block 2*mb + wm), so a tile with few
+        // rows still splits evenly.  Blocks past the tile's rows are skipped -- matrix instructions, fragment
+        // reads and stores: the tile body is compiled once per number of blocks this wavefront owns.
+        const int my_blocks = (((cur_nrows + 31) >> 5) - wm + 1) >> 1;
+        auto run_tile = [&](auto myb_c) {
+        constexpr int MYB = decltype(myb_c)::value;
+        f32x16_t acc[4][4];
+        zero_acc<4, 4>(acc);
         {
-            // stage 0 landed: everything but the NS-1 younger stages -- and the 32 stores of the previous
+            // stage 0 landed: everything but the NS-1 younger stages -- and the stores of the previous
             // tile's epilogue, which are younger still
-            if (first) MOE_VMCNT((NS - 1) * 8);
-            else MOE_VMCNT((NS - 1) * 8 + 32);
+            MOE_VMCNT_PLUS((NS - 1) * 8, prev_stores);
             __builtin_amdgcn_s_barrier();
             const unsigned a = a_addr[0] + buf * (STAGE * 16), b = b_addr[0] + buf * (STAGE * 16);
-            MOE_DS_READ128(fx[0], a, 0); MOE_DS_READ128(fx[1], a, 2048); MOE_DS_READ128(fx[2], a, 4096); MOE_DS_READ128(fx[3], a, 6144);
+            if (0 < MYB) MOE_DS_READ128(fx[0], a, 0); if (1 < MYB) MOE_DS_READ128(fx[1], a, 4096); if (2 < MYB) MOE_DS_READ128(fx[2], a, 8192); if (3 < MYB) MOE_DS_READ128(fx[3], a, 12288);
             MOE_DS_READ128(fx[4], b, 0); MOE_DS_READ128(fx[5], b, 2048); MOE_DS_READ128(fx[6], b, 4096); MOE_DS_READ128(fx[7], b, 6144);
             MOE_WAIT_LGKM0_8(fx);
         }
-        const int cur_row0 = row0, cur_nrows = nrows, cur_nt = nt;
         for (int kc = 0; kc < nk; ++kc) {
             {   // first 16-deep step of the stage; fetch the fragments of the second
                 const unsigned a = a_addr[1] + buf * (STAGE * 16), b = b_addr[1] + buf * (STAGE * 16);
-                MOE_MF(fx, 0, 0); MOE_DS_READ128(fy[0], a, 0); MOE_SB();
+                MOE_MF(fx, 0, 0); if (0 < MYB) MOE_DS_READ128(fy[0], a, 0); MOE_SB();
                 MOE_MF(fx, 0, 1); MOE_DS_READ128(fy[4], b, 0); MOE_SB();
                 MOE_MF(fx, 0, 2); MOE_DS_READ128(fy[5], b, 2048); MOE_SB();
                 MOE_MF(fx, 0, 3); MOE_DS_READ128(fy[6], b, 4096); MOE_SB();
                 MOE_MF(fx, 1, 0); MOE_DS_READ128(fy[7], b, 6144); MOE_SB();
-                MOE_MF(fx, 1, 1); MOE_DS_READ128(fy[1], a, 2048); MOE_SB();
-                MOE_MF(fx, 1, 2); MOE_DS_READ128(fy[2], a, 4096); MOE_SB();
-                MOE_MF(fx, 1, 3); MOE_DS_READ128(fy[3], a, 6144); MOE_SB();
+                MOE_MF(fx, 1, 1); if (1 < MYB) MOE_DS_READ128(fy[1], a, 4096); MOE_SB();
+                MOE_MF(fx, 1, 2); if (2 < MYB) MOE_DS_READ128(fy[2], a, 8192); MOE_SB();
+                MOE_MF(fx, 1, 3); if (3 < MYB) MOE_DS_READ128(fy[3], a, 12288); MOE_SB();
                 MOE_MF(fx, 2, 0); MOE_MF(fx, 2, 1); MOE_MF(fx, 2, 2); MOE_MF(fx, 2, 3);
                 MOE_MF(fx, 3, 0); MOE_MF(fx, 3, 1); MOE_MF(fx, 3, 2); MOE_MF(fx, 3, 3); MOE_SB();
             }
@@ -211,8 +233,8 @@ __device__ __forceinline__ void dense_tiles_bf16(const bf16_t *__restrict__ A, c
             // stage kc+1 landed (this wavefront's part); the barrier makes that true for all four and
             // tells that everyone has read stage kc, whose buffer is refilled below.  Stages up to NS-1
             // of a tile were issued before the previous epilogue's stores.
-            if (first || kc + 2 > NS) MOE_VMCNT((NS - 2) * 8);
-            else MOE_VMCNT((NS - 2) * 8 + 32);
+            if (kc + 2 > NS) MOE_VMCNT((NS - 2) * 8);
+            else MOE_VMCNT_PLUS((NS - 2) * 8, prev_stores);
             __builtin_amdgcn_s_barrier();
             MOE_SB();
             {
@@ -239,14 +261,14 @@ __device__ __forceinline__ void dense_tiles_bf16(const bf16_t *__restrict__ A, c
                 MOE_MF(fy, 1, 1); MOE_LB(1); MOE_SB();
                 MOE_MF(fy, 1, 2); MOE_LB(2); MOE_SB();
                 MOE_MF(fy, 1, 3); MOE_LB(3); MOE_SB();
-                MOE_MF(fy, 2, 0); MOE_DS_READ128(fx[0], a, 0); MOE_SB();
+                MOE_MF(fy, 2, 0); if (0 < MYB) MOE_DS_READ128(fx[0], a, 0); MOE_SB();
                 MOE_MF(fy, 2, 1); MOE_DS_READ128(fx[4], b, 0); MOE_SB();
                 MOE_MF(fy, 2, 2); MOE_DS_READ128(fx[5], b, 2048); MOE_SB();
                 MOE_MF(fy, 2, 3); MOE_DS_READ128(fx[6], b, 4096); MOE_SB();
                 MOE_MF(fy, 3, 0); MOE_DS_READ128(fx[7], b, 6144); MOE_SB();
-                MOE_MF(fy, 3, 1); MOE_DS_READ128(fx[1], a, 2048); MOE_SB();
-                MOE_MF(fy, 3, 2); MOE_DS_READ128(fx[2], a, 4096); MOE_SB();
-                MOE_MF(fy, 3, 3); MOE_DS_READ128(fx[3], a, 6144); MOE_SB();
+                MOE_MF(fy, 3, 1); if (1 < MYB) MOE_DS_READ128(fx[1], a, 4096); MOE_SB();
+                MOE_MF(fy, 3, 2); if (2 < MYB) MOE_DS_READ128(fx[2], a, 8192); MOE_SB();
+                MOE_MF(fy, 3, 3); if (3 < MYB) MOE_DS_READ128(fx[3], a, 12288); MOE_SB();
 #undef MOE_LA
 #undef MOE_LB
             }
@@ -259,6 +281,7 @@ __device__ __forceinline__ void dense_tiles_bf16(const bf16_t *__restrict__ A, c
         const unsigned rd_addr = strip + ((lane >> 4) * LDE + (lane & 15) * 8) * 2;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
+            if (mb >= MYB) continue;
             typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
             typedef float f32x2_t __attribute__((ext_vector_type(2)));
 #define MOE_PK(nb, q)                                                                                                \
@@ -293,16 +316,24 @@ __device__ __forceinline__ void dense_tiles_bf16(const bf16_t *__restrict__ A, c
             MOE_WAIT_LGKM0_8(o);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int gr = wm * 128 + mb * 32 + i * 4 + (lane >> 4);
+                const int gr = (2 * mb + wm) * 32 + i * 4 + (lane >> 4);
                 // always 8 stores per block, so the counted waits of the next tile hold: rows past the
                 // tile rewrite its last row with the same values (the clamped loads duplicated it)
                 const int sr = gr < cur_nrows ? gr : cur_nrows - 1;
                 *reinterpret_cast<u32x4_t *>(C + (size_t)(cur_row0 + sr) * N + cur_nt * DENSE_BN + wn * 128 + (lane & 15) * 8) = o[i];
             }
         }
+        };   // run_tile
+        switch (my_blocks) {
+        case 0: run_tile(std::integral_constant<int, 0>{}); break;
+        case 1: run_tile(std::integral_constant<int, 1>{}); break;
+        case 2: run_tile(std::integral_constant<int, 2>{}); break;
+        case 3: run_tile(std::integral_constant<int, 3>{}); break;
+        default: run_tile(std::integral_constant<int, 4>{}); break;
+        }
         if (!has_next) break;
         lin = next;
-        first = false;
+        prev_stores = 8 * my_blocks;
     }
 #undef MOE_MF
     MOE_VMCNT(0);
