@@ -396,10 +396,10 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
     // both products must take the dense route or neither: the lists split the rows once
     const bool dense = dtype == MOE_BF16 && ffn_use_dense(max_rows, max_slots, d, F, schedule) &&
                        ffn_use_dense(max_rows, max_slots, F, d, schedule);
-    // The 128-row tile of the 128-column kernel is for long slots the dense kernel does not take (small
-    // batches, shapes outside its tiling).  With the dense kernel on, or with slots that can hold 64 rows
-    // on average at most, work items are cut 64 rows high and the leaner build of the kernel runs.
-    const bool tall = dtype == MOE_BF16 && !dense && (long long)max_rows > 64LL * max_slots;
+    // Without the dense kernel (small batches, short slots on average, shapes outside its tiling, the
+    // experts schedule) the 128-column kernel cuts work items 128 rows high and picks the tile height per
+    // item; with it, only pieces of at most 64 rows are left and the leaner build runs.
+    const bool tall = dtype == MOE_BF16 && !dense;
     const int tile_rows = tall ? FFN_BM_TALL : FFN_BM;
     hipLaunchKernelGGL(ffn_worklist_kernel, dim3(1), dim3(1024), 0, st, slot_offset, slot_expert, n_slots, max_slots,
                        max_items, schedule, tile_rows, E, dense ? 1 : 0, max_dense, items, dtiles, n_items);
