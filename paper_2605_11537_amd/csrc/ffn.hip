@@ -404,8 +404,10 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
     hipLaunchKernelGGL(ffn_worklist_kernel, dim3(1), dim3(1024), 0, st, slot_offset, slot_expert, n_slots, max_slots,
                        max_items, schedule, tile_rows, E, dense ? 1 : 0, max_dense, items, dtiles, n_items);
     MOE_CHECK_LAUNCH("moe_expert_ffn/worklist");
-    int grid_items = schedule == MOE_SCHEDULE_SLOTS ? max_slots + max_rows / tile_rows + 1
-                                                    : (max_slots < max_items ? max_slots : max_items);
+    // upper bounds of the 128-column kernel's list: with the dense kernel on, a slot leaves it one piece at most
+    int grid_items = schedule != MOE_SCHEDULE_SLOTS ? (max_slots < max_items ? max_slots : max_items)
+                     : dense                        ? max_slots
+                                                    : max_slots + max_rows / tile_rows + 1;
     hipEvent_t ev[3] = {g_timing_ev[0], g_timing_ev[1], g_timing_ev[2]};
     g_timing_ev[0] = g_timing_ev[1] = g_timing_ev[2] = nullptr;
     if (ev[0]) (void)hipEventRecord(ev[0], st);

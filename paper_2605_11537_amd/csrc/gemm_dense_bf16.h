@@ -9,7 +9,8 @@
 // 16 accumulator blocks = 256 registers, so one workgroup lives on a CU (one wavefront per SIMD).
 //
 // Data path.  Both operands go global -> LDS directly (global_load_lds, 16 bytes per lane, no
-// register round trip) into a ring of NS stages of 32 k each.  A stage holds 16 token units and 16
+// register round trip) into a ring of NS = 4 stages of 32 k each (128 KB: three stages, 48 KB of
+// weights, in flight per CU -- the ring depth is what a tile that streams its weights from HBM runs on).  A stage holds 16 token units and 16
 // weight units of 1 KB; a unit is what one wavefront-wide load writes (64 lanes x 16 bytes, in lane
 // order):
 //   weight unit (strip s, step ks): the 1 KB of the packed weight image that IS the matrix-core
@@ -38,9 +39,9 @@
 namespace moe {
 
 constexpr int DENSE_BM = 256, DENSE_BN = 256, DENSE_BK = 32;
-constexpr int DENSE_NS = 3;                                   // stages in the ring
+constexpr int DENSE_NS = 4;                                   // stages in the ring
 constexpr int DENSE_STAGE = 32 * 64;                          // 16-byte pieces per stage
-constexpr int DENSE_LDE = 128 + 8;                            // epilogue strip row stride (elements)
+constexpr int DENSE_LDE = 64 + 8;                             // epilogue strip (32 rows x 64 columns) row stride, elements
 constexpr int DENSE_IDX_OFFSET = DENSE_NS * DENSE_STAGE * 16 + 4 * 32 * DENSE_LDE * 2;   // 256 gathered row numbers
 constexpr int DENSE_LDS_BYTES = DENSE_IDX_OFFSET + 256 * 4;
 constexpr int DENSE_MIN_K = 256;                              // the pipeline needs a few stages per tile
@@ -274,54 +275,56 @@ __device__ __forceinline__ void dense_tiles_bf16(const bf16_t *__restrict__ A, c
             }
             MOE_WAIT_LGKM0_8(fx);
         }
-        // epilogue: this wavefront's 128 x 128 part, one block of 32 token rows at a time through its own
+        // epilogue: this wavefront's 128 x 128 part, 32 token rows x 64 columns at a time through its own
         // LDS strip (transposes lane-per-column into 16-byte row pieces)
         const unsigned strip = lds0 + NS * STAGE * 16 + w * (32 * LDE * 2);
         const unsigned wr_addr = strip + ((lane & 31) * LDE + 4 * (lane >> 5)) * 2;
-        const unsigned rd_addr = strip + ((lane >> 4) * LDE + (lane & 15) * 8) * 2;
+        const unsigned rd_addr = strip + ((lane >> 3) * LDE + (lane & 7) * 8) * 2;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
             if (mb >= MYB) continue;
             typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
             typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// volatile asm: an ordinary max here is hoisted by the compiler onto the whole accumulator array right
+// after the k loop, which needs 256 more registers and spills
+#define MOE_RELU_BITS(f) ({ float r_; asm volatile("v_max_i32 %0, 0, %1" : "=v"(r_) : "v"((float)(f))); r_; })
 #define MOE_PK(nb, q)                                                                                                \
     ({                                                                                                               \
         f32x2_t lo = {acc[mb][nb][4 * q], acc[mb][nb][4 * q + 1]}, hi = {acc[mb][nb][4 * q + 2], acc[mb][nb][4 * q + 3]}; \
+        if (RELU) { /* as signed integers: anything with the sign bit set becomes +0 */                             \
+            lo.x = MOE_RELU_BITS(lo.x); lo.y = MOE_RELU_BITS(lo.y); hi.x = MOE_RELU_BITS(hi.x); hi.y = MOE_RELU_BITS(hi.y); \
+        }                                                                                                            \
         uint2 pk;                                                                                                    \
         pk.x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2_t));                                  \
         pk.y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2_t));                                  \
-        if (RELU) { /* on the packed pairs: clear every half whose sign bit is set */                              \
-            pk.x &= ~(((pk.x >> 15) & 0x00010001u) * 0xFFFFu);                                                       \
-            pk.y &= ~(((pk.y >> 15) & 0x00010001u) * 0xFFFFu);                                                       \
-        }                                                                                                            \
         pk;                                                                                                          \
     })
-            {
-                uint2 v;   // block nb, group q -> columns nb*32 + 8q + 4*(lane/32) .. +3 of token row lane%32
-                v = MOE_PK(0, 0); MOE_DS_WRITE64(wr_addr, v, 0);   v = MOE_PK(0, 1); MOE_DS_WRITE64(wr_addr, v, 16);
-                v = MOE_PK(0, 2); MOE_DS_WRITE64(wr_addr, v, 32);  v = MOE_PK(0, 3); MOE_DS_WRITE64(wr_addr, v, 48);
-                v = MOE_PK(1, 0); MOE_DS_WRITE64(wr_addr, v, 64);  v = MOE_PK(1, 1); MOE_DS_WRITE64(wr_addr, v, 80);
-                v = MOE_PK(1, 2); MOE_DS_WRITE64(wr_addr, v, 96);  v = MOE_PK(1, 3); MOE_DS_WRITE64(wr_addr, v, 112);
-                v = MOE_PK(2, 0); MOE_DS_WRITE64(wr_addr, v, 128); v = MOE_PK(2, 1); MOE_DS_WRITE64(wr_addr, v, 144);
-                v = MOE_PK(2, 2); MOE_DS_WRITE64(wr_addr, v, 160); v = MOE_PK(2, 3); MOE_DS_WRITE64(wr_addr, v, 176);
-                v = MOE_PK(3, 0); MOE_DS_WRITE64(wr_addr, v, 192); v = MOE_PK(3, 1); MOE_DS_WRITE64(wr_addr, v, 208);
-                v = MOE_PK(3, 2); MOE_DS_WRITE64(wr_addr, v, 224); v = MOE_PK(3, 3); MOE_DS_WRITE64(wr_addr, v, 240);
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                {
+                    uint2 v;   // block nb, group q -> columns (nb%2)*32 + 8q + 4*(lane/32) .. +3 of token row lane%32
+                    v = MOE_PK(2 * half, 0); MOE_DS_WRITE64(wr_addr, v, 0);       v = MOE_PK(2 * half, 1); MOE_DS_WRITE64(wr_addr, v, 16);
+                    v = MOE_PK(2 * half, 2); MOE_DS_WRITE64(wr_addr, v, 32);      v = MOE_PK(2 * half, 3); MOE_DS_WRITE64(wr_addr, v, 48);
+                    v = MOE_PK(2 * half + 1, 0); MOE_DS_WRITE64(wr_addr, v, 64);  v = MOE_PK(2 * half + 1, 1); MOE_DS_WRITE64(wr_addr, v, 80);
+                    v = MOE_PK(2 * half + 1, 2); MOE_DS_WRITE64(wr_addr, v, 96);  v = MOE_PK(2 * half + 1, 3); MOE_DS_WRITE64(wr_addr, v, 112);
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                u32x4_t o[4];      // rows 8i + lane/8 of the strip: row stride 8 * LDE * 2 = 1152 bytes
+                MOE_DS_READ128(o[0], rd_addr, 0);    MOE_DS_READ128(o[1], rd_addr, 1152);
+                MOE_DS_READ128(o[2], rd_addr, 2304); MOE_DS_READ128(o[3], rd_addr, 3456);
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3])::"memory");
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int gr = (2 * mb + wm) * 32 + i * 8 + (lane >> 3);
+                    // always 8 stores per block, so the counted waits of the next tile hold: rows past the
+                    // tile rewrite its last row with the same values (the clamped loads duplicated it)
+                    const int sr = gr < cur_nrows ? gr : cur_nrows - 1;
+                    *reinterpret_cast<u32x4_t *>(C + (size_t)(cur_row0 + sr) * N + cur_nt * DENSE_BN + wn * 128 + half * 64 +
+                                                 (lane & 7) * 8) = o[i];
+                }
             }
 #undef MOE_PK
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            u32x4_t o[8];      // rows 4i + lane/16 of the strip: row stride 4 * LDE * 2 = 1088 bytes
-            MOE_DS_READ128(o[0], rd_addr, 0);    MOE_DS_READ128(o[1], rd_addr, 1088); MOE_DS_READ128(o[2], rd_addr, 2176);
-            MOE_DS_READ128(o[3], rd_addr, 3264); MOE_DS_READ128(o[4], rd_addr, 4352); MOE_DS_READ128(o[5], rd_addr, 5440);
-            MOE_DS_READ128(o[6], rd_addr, 6528); MOE_DS_READ128(o[7], rd_addr, 7616);
-            MOE_WAIT_LGKM0_8(o);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int gr = (2 * mb + wm) * 32 + i * 4 + (lane >> 4);
-                // always 8 stores per block, so the counted waits of the next tile hold: rows past the
-                // tile rewrite its last row with the same values (the clamped loads duplicated it)
-                const int sr = gr < cur_nrows ? gr : cur_nrows - 1;
-                *reinterpret_cast<u32x4_t *>(C + (size_t)(cur_row0 + sr) * N + cur_nt * DENSE_BN + wn * 128 + (lane & 15) * 8) = o[i];
-            }
+#undef MOE_RELU_BITS
         }
         };   // run_tile
         switch (my_blocks) {
