@@ -179,7 +179,8 @@ int moe_pack_weights(const void *w, int E, int K, int N, int dtype, void *w_pack
  * from x_perm[row_index[r]] -- pass the token matrix x as x_perm and moe_dispatch's perm as
  * row_index, and call moe_dispatch with x = x_perm = NULL: the permuted copy of the tokens is
  * then never written to HBM.  x_perm must hold max_rows rows; an index outside [0, max_rows)
- * reads as a zero row.  y_perm stays in permuted row order either way.
+ * is never dereferenced (the row is computed from a zero row or from row 0, its output is
+ * unspecified).  y_perm stays in permuted row order either way.
  */
 size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, int d, int F, int dtype);
 int moe_expert_ffn(const void *x_perm, const int32_t *row_index, const void *w1, const void *w2,

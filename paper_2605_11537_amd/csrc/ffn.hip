@@ -158,7 +158,9 @@ template <bool RELU, bool TALL>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void ffn_gemm_bf16_kernel(
     const bf16_t *__restrict__ A, const int32_t *__restrict__ row_index, int n_src_rows,
     const bf16_t *__restrict__ Wp, int K, int N, int E, const WorkItem *__restrict__ items,
-    const int32_t *__restrict__ n_items, int max_rows, bf16_t *__restrict__ C)
+    const int32_t *__restrict__ n_items, const int32_t *__restrict__ slot_offset,
+    const int32_t *__restrict__ slot_expert, const int32_t *__restrict__ n_slots_p, int max_slots, int schedule,
+    int max_rows, bf16_t *__restrict__ C)
 {
     constexpr int TM = TALL ? FFN_BM_TALL : FFN_BM;          // rows per pass over a work item
     constexpr int MBT = TM / 32;
@@ -167,8 +169,33 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void ffn_gemm_bf16_kernel(
     __shared__ __attribute__((aligned(16))) bf16_t lds[(S0 > S1 ? S0 : S1) > S2 ? (S0 > S1 ? S0 : S1) : S2];
     const int n_nt = N / FFN_BN;
     int item, nt;
-    if (!grouped_tile_of(blockIdx.x, n_items[0], n_nt, n_items[1], item, nt)) return;
-    const WorkItem it = items[item];
+    WorkItem it;
+    if (items) {
+        if (!grouped_tile_of(blockIdx.x, n_items[0], n_nt, n_items[1], item, nt)) return;
+        it = items[item];
+    } else {
+        // No list: one work item per slot (per expert in the experts schedule), read straight from the
+        // slot tables; a range longer than the tile is walked by the loop below.  Saves the list kernel
+        // where slots are short anyway; the 8 contiguous XCD ranges are taken over all slots.
+        int P = n_slots_p[0];
+        if (P > max_slots) P = max_slots;
+        const int lid = xcd_remap(blockIdx.x, P * n_nt);
+        if (lid < 0) return;
+        item = lid / n_nt;
+        nt = lid - item * n_nt;
+        const int e = slot_expert[item];
+        it.expert = e;
+        it.row_begin = slot_offset[item];
+        const bool after_same = item > 0 && slot_expert[item - 1] == e;
+        int last = item;
+        if (schedule == MOE_SCHEDULE_EXPERTS) {
+            if (after_same) return;                       // the expert's first slot walks all its rows
+            while (last + 1 < P && slot_expert[last + 1] == e) ++last;
+        }
+        it.row_end = slot_offset[last + 1];
+        it.reuse = it.row_end - it.row_begin > TM || (schedule == MOE_SCHEDULE_SLOTS &&
+                                                     (after_same || (item + 1 < P && slot_expert[item + 1] == e)));
+    }
     if (it.expert < 0 || it.expert >= E || it.row_begin < 0) return;  // never index weights with a bad id
     const bf16_t *Bp = Wp + (size_t)it.expert * K * N;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -401,12 +428,21 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
     // item; with it, only pieces of at most 64 rows are left and the leaner build runs.
     const bool tall = dtype == MOE_BF16 && !dense;
     const int tile_rows = tall ? FFN_BM_TALL : FFN_BM;
-    hipLaunchKernelGGL(ffn_worklist_kernel, dim3(1), dim3(1024), 0, st, slot_offset, slot_expert, n_slots, max_slots,
-                       max_items, schedule, tile_rows, E, dense ? 1 : 0, max_dense, items, dtiles, n_items);
-    MOE_CHECK_LAUNCH("moe_expert_ffn/worklist");
+    // Slots that hold 64 rows on average at most are one tile each, give or take: the 128-column kernel
+    // then reads the slot tables itself and the list kernel (a launch of ~5 us in front of the first
+    // product) is skipped.  Long slots without the dense kernel keep the list: it cuts them into tiles
+    // that run side by side.
+    const bool listless = dtype == MOE_BF16 && !dense && (long long)max_rows <= 64LL * max_slots;
+    if (!listless) {
+        hipLaunchKernelGGL(ffn_worklist_kernel, dim3(1), dim3(1024), 0, st, slot_offset, slot_expert, n_slots,
+                           max_slots, max_items, schedule, tile_rows, E, dense ? 1 : 0, max_dense, items, dtiles,
+                           n_items);
+        MOE_CHECK_LAUNCH("moe_expert_ffn/worklist");
+    }
+    const WorkItem *list = listless ? nullptr : items;
     // upper bounds of the 128-column kernel's list: with the dense kernel on, a slot leaves it one piece at most
     int grid_items = schedule != MOE_SCHEDULE_SLOTS ? (max_slots < max_items ? max_slots : max_items)
-                     : dense                        ? max_slots
+                     : (dense || listless)          ? max_slots
                                                     : max_slots + max_rows / tile_rows + 1;
     hipEvent_t ev[3] = {g_timing_ev[0], g_timing_ev[1], g_timing_ev[2]};
     g_timing_ev[0] = g_timing_ev[1] = g_timing_ev[2] = nullptr;
@@ -431,12 +467,14 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
         }
         if (tall)
             hipLaunchKernelGGL((ffn_gemm_bf16_kernel<true, true>), dim3(g1), dim3(GEMM_THREADS), 0, st,
-                               (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, E, items,
-                               n_items, max_rows, (bf16_t *)h);
+                               (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, E, list,
+                               n_items, slot_offset, slot_expert, n_slots, max_slots, schedule, max_rows,
+                               (bf16_t *)h);
         else
             hipLaunchKernelGGL((ffn_gemm_bf16_kernel<true, false>), dim3(g1), dim3(GEMM_THREADS), 0,
-                               st, (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, E, items,
-                               n_items, max_rows, (bf16_t *)h);
+                               st, (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, E, list,
+                               n_items, slot_offset, slot_expert, n_slots, max_slots, schedule, max_rows,
+                               (bf16_t *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
         if (ev[1]) (void)hipEventRecord(ev[1], st);
         if (dense) {
@@ -448,11 +486,13 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
         if (tall)
             hipLaunchKernelGGL((ffn_gemm_bf16_kernel<false, true>), dim3(g2), dim3(GEMM_THREADS), 0, st,
                                (const bf16_t *)h, (const int32_t *)nullptr, max_rows, (const bf16_t *)w2, F, d, E,
-                               items, n_items, max_rows, (bf16_t *)y_perm);
+                               list, n_items, slot_offset, slot_expert, n_slots, max_slots, schedule, max_rows,
+                               (bf16_t *)y_perm);
         else
             hipLaunchKernelGGL((ffn_gemm_bf16_kernel<false, false>), dim3(g2), dim3(GEMM_THREADS), 0,
                                st, (const bf16_t *)h, (const int32_t *)nullptr, max_rows, (const bf16_t *)w2, F, d, E,
-                               items, n_items, max_rows, (bf16_t *)y_perm);
+                               list, n_items, slot_offset, slot_expert, n_slots, max_slots, schedule, max_rows,
+                               (bf16_t *)y_perm);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm2");
     } else {
         int g1 = grid_items * (F / 64), g2 = grid_items * (d / 64);
