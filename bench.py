@@ -205,6 +205,22 @@ def main():
                     ffn_mfma_tflops=round(2 * flops / ((g1 + g2) * 1e-3) / 1e12, 2),
                     ffn_mfma_frac_of_bf16_peak=round(2 * flops / ((g1 + g2) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4))
 
+    pipeline = None
+    if sru is not None:
+        # the paper's two threads as two streams: predictor + plan of batch i+1 under the layer of batch i
+        pipe = moe.MoePipeline(layer, sru[1], c["sru"]["B"], c["sru"]["L"])
+        pipe.predict(sru[0])
+
+        def step_pipelined():
+            pipe.predict(sru[0])
+            pipe.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED)
+
+        for _ in range(a.warmup):
+            step_pipelined()
+        ms_pipe = _time_steps(step_pipelined, a.steps)
+        pipeline = {"ms_per_step": round(ms_pipe, 5), "tokens_per_s": round(T / (ms_pipe * 1e-3), 1),
+                    "note": "sru_predict + replica_plan of the next batch on a second stream"}
+
     modes = {"on": round(T / (ms_on * 1e-3), 1)}
     extra_ms = {"on": round(ms_on, 5)}
     for name, fn in (("off_same_plan", step_off_same_plan), ("off_budget0", step_off_budget0)):
@@ -243,6 +259,8 @@ def main():
         "ms_per_step_with_kernel_events": round(ms_on_events, 5),
         "kept_tokens_budget0": kept0,
     }
+    if pipeline is not None:
+        line["two_stream_pipeline"] = pipeline
     print(json.dumps(line))
 
 

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     SCHEDULE_SLOTS,
     MoeError,
     MoeLayer,
+    MoePipeline,
     SruWeights,
     lib,
     moe_combine,

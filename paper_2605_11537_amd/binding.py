@@ -268,17 +268,65 @@ class MoeLayer:
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
 
     def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
-                out=None, budget=None, router_layout=LAYOUT_PLAIN, fuse_gather=True):
+                out=None, budget=None, router_layout=LAYOUT_PLAIN, fuse_gather=True, plan=None):
+        """plan: tables of a replica_plan call made earlier (e.g. by MoePipeline on another stream);
+        otherwise the plan is computed here from plan_ids, or from the router's own ids."""
         idx, prob, _ = moe_route(x, w_router, b_router, out=self.route_out, ws=self.route_ws,
                                  w_layout=router_layout)
         R = self.R if budget is None else budget
         if R != self.R:
             raise ValueError("budget is fixed by the preallocated slot tables")
-        pl = replica_plan(idx if plan_ids is None else plan_ids, self.E, R, self.C, self.policy, out=self.plan_out,
-                          ws=self.plan_ws)
+        pl = plan if plan is not None else replica_plan(idx if plan_ids is None else plan_ids, self.E, R, self.C,
+                                                        self.policy, out=self.plan_out, ws=self.plan_ws)
         dp = moe_dispatch(None if fuse_gather else x, idx, pl["replicas"], self.E, self.C, self.max_slots,
                           out=self.disp_out, ws=self.disp_ws, shape=(self.T, self.d), dtype=x.dtype)
         y = moe_expert_ffn(x if fuse_gather else dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"],
                            pl["n_slots"], self.E, self.F, max_slots=self.max_slots, schedule=schedule,
                            out=self.y_perm, ws=self.ffn_ws, row_index=dp["perm"] if fuse_gather else None)
         return moe_combine(y, x, dp["inv"], prob, residual, out=self.out if out is None else out)
+
+
+class MoePipeline:
+    """Predictor and replica plan of batch i+1 on a second stream while the layer of batch i runs
+    (the paper's two threads and their queue of per-batch tables, as two HIP streams and two sets of
+    plan tables).  ``predict(emb)`` enqueues sru_predict + replica_plan for the next batch;
+    ``forward(x, ...)`` runs the layer of the oldest batch predicted and not yet run.  The embeddings
+    must be ready when predict is called (they are not ordered after work on the layer's stream).
+    Both streams have the default priority."""
+
+    def __init__(self, layer: "MoeLayer", sru_weights, B, L):
+        self.layer, self.w, self.B, self.L = layer, sru_weights, B, L
+        dev = layer.out.device
+        E, R, T = layer.E, layer.R, layer.T
+        self.stream = torch.cuda.Stream(device=dev)
+        self.sets = []
+        for _ in range(2):
+            plan = dict(plan_counts=_i32(E, dev), replicas=_i32(E, dev), slot_base=_i32(E + 1, dev),
+                        slot_expert=_i32(E + R, dev), n_slots=_i32(1, dev))
+            self.sets.append(dict(plan=plan, ids=_i32(T, dev), ready=torch.cuda.Event(), free=torch.cuda.Event()))
+        self.sru_ws = _ws(lib().sru_predict_workspace_bytes(C.byref(sru_weights.c), B, L, MOE_BF16), dev)
+        self.plan_ws = _ws(lib().replica_plan_workspace_bytes(T, E), dev)
+        self.n_pred = self.n_run = 0
+
+    def predict(self, emb):
+        if self.n_pred - self.n_run >= 2:
+            raise RuntimeError("two batches are already predicted and waiting for their layer")
+        s = self.sets[self.n_pred % 2]
+        with torch.cuda.stream(self.stream):
+            self.stream.wait_event(s["free"])      # the layer that last read these tables has finished
+            ids, _ = sru_predict(emb, self.w, out=s["ids"], ws=self.sru_ws)
+            replica_plan(ids, self.layer.E, self.layer.R, self.layer.C, self.layer.policy, out=s["plan"],
+                         ws=self.plan_ws)
+            s["ready"].record(self.stream)
+        self.n_pred += 1
+
+    def forward(self, x, w_router, b_router, w1, w2, **kw):
+        if self.n_run >= self.n_pred:
+            raise RuntimeError("no predicted batch is waiting")
+        s = self.sets[self.n_run % 2]
+        main = torch.cuda.current_stream()
+        main.wait_event(s["ready"])
+        out = self.layer.forward(x, w_router, b_router, w1, w2, plan=s["plan"], **kw)
+        s["free"].record(main)
+        self.n_run += 1
+        return out

@@ -83,3 +83,43 @@ def test_sru_config3_and_predictor_driven_layer():
     r = synth.storage_to_f64(full["out"])[toks]
     assert np.abs(g - r).max() <= 2e-2 * np.abs(r).max()
     print(f"config 3: router/predictor agreement {agree:.3f}, kept {K}/{T}", flush=True)
+
+
+def test_two_stream_pipeline_equals_sequential():
+    """Predictor + plan of batch i+1 on a second stream under the layer of batch i: every batch must
+    come out bit for bit as when the same calls run one after the other on one stream.  Batches
+    differ (fresh embeddings at different scales, tokens rolled) so that a plan table read too early
+    or too late would show."""
+    import paper_2605_11537_amd as moe
+    s = synth.sru_inputs(4, 256, 128, 128, 2, 16, synth.BF16, 901, bias_std=0.2, w_std=0.08)
+    T, E, d, F, C, R = 4 * 256, 16, 128, 256, 48, 6
+    c = synth.moe_layer_inputs(T, d, F, E, synth.BF16, 1.1, 902)
+    w = moe.SruWeights([to_dev(a) for a in s["w_cat"]], [to_dev(a) for a in s["b_f"]], [to_dev(a) for a in s["b_r"]],
+                       to_dev(s["w_head"]), to_dev(s["b_head"]))
+    wr, b = to_dev(c["w_router"]), to_dev(c["b_router"])
+    w1, w2 = moe.moe_pack_weights(to_dev(c["w1"])), moe.moe_pack_weights(to_dev(c["w2"]))
+    emb0, x0 = to_dev(s["emb"]), to_dev(c["x"])
+    n_batches = 7
+    embs = [emb0] + [to_dev(synth.normal_tensor((4, 256, 128), 2.0 ** (i % 3 - 1), [903, i], synth.BF16))
+                     for i in range(1, n_batches)]
+    xs = [torch.roll(x0, shifts=31 * i, dims=0).contiguous() for i in range(n_batches)]
+    layer = moe.MoeLayer(T, d, F, E, R, C, torch.bfloat16)
+    seq = []
+    for i in range(n_batches):
+        ids, _ = moe.sru_predict(embs[i], w)
+        seq.append(layer.forward(xs[i], wr, b, w1, w2, plan_ids=ids).clone())
+    torch.cuda.synchronize()
+    plans = {tuple(to_host(moe.replica_plan(moe.sru_predict(e, w)[0], E, R, C)["replicas"])) for e in embs}
+    assert len(plans) > 1                                   # the batches really ask for different plans
+    pipe = moe.MoePipeline(layer, w, 4, 256)
+    outs = []
+    pipe.predict(embs[0])
+    for i in range(n_batches):
+        if i + 1 < n_batches:
+            pipe.predict(embs[i + 1])
+        outs.append(pipe.forward(xs[i], wr, b, w1, w2).clone())
+    torch.cuda.synchronize()
+    for i in range(n_batches):
+        assert torch.equal(outs[i], seq[i]), f"batch {i}"
+    with pytest.raises(RuntimeError):
+        pipe.forward(xs[0], wr, b, w1, w2)                  # nothing predicted is waiting
