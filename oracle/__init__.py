@@ -111,6 +111,28 @@ def sru(emb, w_cat, b_f, b_r, w_head, b_head=None):
     return dict(pred=pred, logits=logits, idx2=idx2, margin=margin, h=h)
 
 
+def sru_attention(emb, w_cat, b_f, b_r, w_head, b_head=None):
+    """The SRU predictor with sparsemax attention over its last layer's states
+    (``oracle/sparse_attention.py`` states the reading).  -> dict(pred, logits, idx2, margin, h, z)."""
+    import synth
+    from . import sparse_attention as sa
+    base = sru(emb, w_cat, b_f, b_r, w_head, b_head)
+    B, L, _ = emb.shape
+    st = _st(emb)
+    def to_storage(a):
+        if st == 0:
+            return a.astype(np.float32)
+        # float64 -> bf16 in one rounding (nearest, ties to even): 8 significant bits
+        m, e = np.frexp(a)
+        r = np.ldexp(np.rint(np.ldexp(m, 8)), e - 8)        # exactly representable in binary32 and in bf16
+        return (r.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+    z = sa.attend(base["h"], B, L, synth.storage_to_f64, to_storage)
+    out = sa.head(z, w_head, b_head, synth.storage_to_f64)
+    out["h"], out["z"] = base["h"], z
+    return out
+
+
 def plan(idx, E, R, C_, policy=0):
     """-> dict(counts[E], replicas[E], slot_base[E+1], slot_expert[E+R], n_slots)."""
     idx = np.ascontiguousarray(idx, np.int32)
