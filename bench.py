@@ -7,7 +7,7 @@ sru_predict in front, its ids driving the plan).  Default workload: the Switch-b
 layer (T=4096, d=768, F=3072, E=128, capacity factor 1.25, replica budget 16, bf16 with fp32
 accumulation), Zipf(1.0)-skewed routing.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg4b|cfg5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3x|cfg4|cfg4b|cfg5]
 """
 from __future__ import annotations
 
@@ -55,6 +55,13 @@ def _workload(name):
         c["sru"] = synth.config_inputs(3)["sru"]
         return c, c["C"], ("2-layer SRU predictor (B=8 L=512 768->256, head 128) + Switch-base-128 layer "
                            "T=4096 d=768 F=3072 E=128 CF=1.25 R=16")
+    if name == "cfg3x":
+        # the paper's predictor size: 10 SRU layers and the sparsemax attention in front of the head
+        c = synth.config_inputs(2)
+        c["sru"] = synth.sru_inputs(8, 512, 768, 256, 10, 128, synth.BF16, synth.workloads.SEED0 + 33, w_std=0.05)
+        c["sru"]["attention"] = True
+        return c, c["C"], ("10-layer SRU predictor with sparsemax attention (B=8 L=512 768->256, head 128) + "
+                           "Switch-base-128 layer T=4096 d=768 F=3072 E=128 CF=1.25 R=16")
     if name == "cfg4":
         c = synth.config_inputs(4)
         return c, c["C"], "Switch-base-256 layer T=16384 d=768 F=3072 E=256 CF=1.0 R=32 Zipf(1.1)"
@@ -146,7 +153,8 @@ def main():
     sru = None
     if "sru" in c:
         s_ = c["sru"]
-        sru_w = moe.SruWeights([_to_dev(w) for w in s_["w_cat"]], None, None, _to_dev(s_["w_head"]), None, pack=True)
+        sru_w = moe.SruWeights([_to_dev(w) for w in s_["w_cat"]], None, None, _to_dev(s_["w_head"]), None, pack=True,
+                               attention=bool(s_.get("attention", False)))
         emb = _to_dev(s_["emb"])
         pred = torch.empty(T, dtype=torch.int32, device="cuda")
         sru_ws = torch.empty(moe.lib().sru_predict_workspace_bytes(__import__("ctypes").byref(sru_w.c), s_["B"],

@@ -99,6 +99,13 @@ typedef struct sru_weights {
     const float *const *b_r;
     const void *w_head;
     const float *b_head;
+    int attention; /* 0: the head reads the last layer's states h_t.  1: sparsemax self-attention first
+                      ("SRU-based predictor with sparse attention", Methodology; SRU subsection, last
+                      paragraph -- the paper prints no equations, this is the reading built): inside
+                      each sequence s[t,j] = <h_t,h_j>/sqrt(n_hidden), a[t,:] = sparsemax(s[t,:]) (the
+                      Euclidean projection onto the simplex: exact zeros for less relevant positions),
+                      z_t = h_t + sum_j a[t,j] h_j rounded to dtype, and the head reads z_t.
+                      Needs L <= 1024 and n_hidden <= 256. */
 } sru_weights;
 
 size_t sru_predict_workspace_bytes(const sru_weights *w, int B, int L, int dtype);

@@ -39,7 +39,8 @@ class MoeError(RuntimeError):
 class SruWeightsC(C.Structure):
     _fields_ = [("n_layers", C.c_int), ("n_in", C.c_int), ("n_hidden", C.c_int), ("n_out", C.c_int),
                 ("w_layout", C.c_int), ("w_cat", C.POINTER(C.c_void_p)), ("b_f", C.POINTER(C.c_void_p)),
-                ("b_r", C.POINTER(C.c_void_p)), ("w_head", C.c_void_p), ("b_head", C.c_void_p)]
+                ("b_r", C.POINTER(C.c_void_p)), ("w_head", C.c_void_p), ("b_head", C.c_void_p),
+                ("attention", C.c_int)]
 
 
 def lib():
@@ -128,9 +129,10 @@ def moe_route(x, w_router, b_router=None, want_logits=False, out=None, ws=None, 
 class SruWeights:
     """Holds the device tensors of an SRU predictor and the host-side C struct naming them."""
 
-    def __init__(self, w_cat, b_f, b_r, w_head, b_head=None, pack=False):
+    def __init__(self, w_cat, b_f, b_r, w_head, b_head=None, pack=False, attention=False):
         """pack=True re-lays the (static) weights once with moe_pack_weights, so that sru_predict
-        does not have to do it on every call (needs n_out = 128 or 256)."""
+        does not have to do it on every call (needs n_out = 128 or 256).  attention=True puts the
+        sparsemax self-attention over the last layer's states in front of the head."""
         if pack:
             w_cat = [moe_pack_weights(w[None].contiguous())[0] for w in w_cat]
             w_head = moe_pack_weights(w_head[None].contiguous())[0]
@@ -147,7 +149,8 @@ class SruWeights:
                              C.cast(self._wc, C.POINTER(C.c_void_p)),
                              C.cast(self._bf, C.POINTER(C.c_void_p)) if self._bf else None,
                              C.cast(self._br, C.POINTER(C.c_void_p)) if self._br else None,
-                             w_head.data_ptr(), b_head.data_ptr() if b_head is not None else None)
+                             w_head.data_ptr(), b_head.data_ptr() if b_head is not None else None,
+                             1 if attention else 0)
 
 
 def sru_predict(emb, weights: SruWeights, want_logits=False, out=None, ws=None):

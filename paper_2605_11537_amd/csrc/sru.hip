@@ -105,7 +105,7 @@ __global__ __launch_bounds__(SRU_CHUNKS * SRU_CHANNELS) void sru_scan_kernel(
 }
 
 struct SruWs {
-    size_t u, h0, h1, wp, rws, prob, total;
+    size_t u, h0, h1, wp, rws, prob, ht, total;
 };
 
 static SruWs sru_ws_layout(const sru_weights *w, int B, int L)
@@ -127,6 +127,8 @@ static SruWs sru_ws_layout(const sru_weights *w, int B, int L)
     off += route_ws_bytes(w->n_hidden, w->n_out, MOE_BF16);
     s.prob = off;
     off += align_up(T * sizeof(float), 256);
+    s.ht = off;
+    if (w->attention) off += sru_attention_ws_bytes(B, L, w->n_hidden);
     s.total = off;
     return s;
 }
@@ -146,6 +148,10 @@ static int sru_check(const sru_weights *w, int B, int L, int dtype)
     MOE_REQUIRE(B <= 65535, MOE_ERR_UNSUPPORTED, "sru_predict: B=%d exceeds 65535", B);
     MOE_REQUIRE(w->w_layout == MOE_LAYOUT_PLAIN || w->w_layout == MOE_LAYOUT_PACKED, MOE_ERR_INVALID_ARG,
                 "sru_predict: unknown weight layout %d", w->w_layout);
+    MOE_REQUIRE(w->attention == 0 || w->attention == 1, MOE_ERR_INVALID_ARG, "sru_predict: attention must be 0 or 1");
+    MOE_REQUIRE(!w->attention || (L <= 1024 && w->n_hidden <= 256), MOE_ERR_UNSUPPORTED,
+                "sru_predict: sparsemax attention needs L <= 1024 and n_hidden <= 256 (L=%d n_hidden=%d)", L,
+                w->n_hidden);
     MOE_REQUIRE(w->w_layout == MOE_LAYOUT_PLAIN ||
                     ((w->n_out == 128 || w->n_out == 256) && w->n_hidden % 128 == 0),
                 MOE_ERR_UNSUPPORTED, "sru_predict: packed weights need n_out = 128 or 256");
@@ -205,6 +211,12 @@ extern "C" int sru_predict(const void *emb, const sru_weights *w, int B, int L, 
         MOE_CHECK_LAUNCH("sru_predict/scan");
         cur = out;
         nin = n_h;
+    }
+    if (w->attention) {
+        bf16_t *zbuf = hbuf[w->n_layers & 1];      // the buffer the last layer did not write
+        rc = sru_attention_launch(cur, B, L, n_h, zbuf, base + lay.ht, st, "sru_predict/attention");
+        if (rc != MOE_OK) return rc;
+        cur = zbuf;
     }
     return route_launch(cur, w->w_head, head_layout, w->b_head, T, n_h, w->n_out, MOE_BF16, pred_idx, (float *)(base + lay.prob),
                         logits_opt, base + lay.rws, st, "sru_predict/head");

@@ -83,7 +83,11 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.moe_combine(p, p, p, p, 4, 64, 0, 2, p, None) == INV                     # residual flag
     assert L.moe_combine(p, q, p, p, 4, 64, 0, 0, q, None) == INV                     # out aliases x
     # sru_predict
-    w = moe.binding.SruWeightsC(2, 768, 256, 128, 0, None, None, None, None, None)
+    w = moe.binding.SruWeightsC(2, 768, 256, 128, 0, None, None, None, None, None, 0)
     assert L.sru_predict(p, C.byref(w), 8, 512, 0, p, None, p, 4096, None) == UNS   # fp32 not built
     assert L.sru_predict(p, C.byref(w), 8, 512, 1, p, None, p, 4096, None) == INV   # null tables
     assert L.sru_predict_workspace_bytes(C.byref(w), 8, 512, 1) > 8 * 512 * 1024 * 4
+    wa = moe.binding.SruWeightsC(2, 768, 256, 128, 0, None, None, None, None, None, 1)
+    assert L.sru_predict(p, C.byref(wa), 8, 2048, 1, p, None, p, 1 << 30, None) == UNS  # attention: L too long
+    wa.attention = 3
+    assert L.sru_predict(p, C.byref(wa), 8, 512, 1, p, None, p, 1 << 30, None) == INV

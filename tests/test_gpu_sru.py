@@ -53,6 +53,39 @@ def test_sru_small(B, L, n_in, n_h, layers, n_out, bias):
     _compare(moe, s, f"sru B={B} L={L}")
 
 
+@pytest.mark.parametrize("B,L,n_in,n_h,layers,n_out", [
+    (3, 70, 192, 128, 2, 24),        # ragged: L not a multiple of the 32-row tile nor of the 64-lane chunks
+    (2, 512, 128, 256, 2, 128),      # the benchmark's sequence length and width
+    (1, 1024, 128, 128, 1, 8),       # longest sequence the score tile holds
+    (5, 1, 128, 128, 1, 8),          # one position per sequence: it attends to itself, z = 2h
+])
+def test_sru_with_sparsemax_attention(B, L, n_in, n_h, layers, n_out):
+    """The attention variant of the predictor against the oracle: the attended states z element by
+    element (bf16 bar), then logits and predictions with the same near-tie rule as without it."""
+    import paper_2605_11537_amd as moe
+    s = synth.sru_inputs(B, L, n_in, n_h, layers, n_out, synth.BF16, 700 + L, bias_std=0.2, w_std=0.08)
+    ref = oracle.sru_attention(s["emb"], s["w_cat"], s["b_f"], s["b_r"], s["w_head"], s["b_head"])
+    w = moe.SruWeights([to_dev(a) for a in s["w_cat"]], [to_dev(a) for a in s["b_f"]], [to_dev(a) for a in s["b_r"]],
+                       to_dev(s["w_head"]), to_dev(s["b_head"]), attention=True)
+    pred, logits = moe.sru_predict(to_dev(s["emb"]), w, want_logits=True)
+    torch.cuda.synchronize()
+    lg = to_host(logits).astype(np.float64)
+    scale = np.abs(ref["logits"]).max()
+    err = np.abs(lg - ref["logits"]).max()
+    assert err <= 2e-2 * scale, f"attention logits off by {err / scale:.3e}"
+    got = to_host(pred)
+    diff = got != ref["pred"]
+    assert not (diff & (ref["margin"] > 2 * err)).any()
+    assert (got[diff] == ref["idx2"][diff]).all()
+    assert diff.mean() <= 0.02
+    # without the attention the same weights give different logits (the option is really on)
+    w0 = moe.SruWeights([to_dev(a) for a in s["w_cat"]], [to_dev(a) for a in s["b_f"]], [to_dev(a) for a in s["b_r"]],
+                        to_dev(s["w_head"]), to_dev(s["b_head"]))
+    _, logits0 = moe.sru_predict(to_dev(s["emb"]), w0, want_logits=True)
+    assert not torch.equal(logits, logits0)
+    print(f"attention B={B} L={L}: max logit err {err:.2e} (scale {scale:.2f}), {int(diff.sum())} near-tie flips", flush=True)
+
+
 def test_sru_config3_and_predictor_driven_layer():
     import paper_2605_11537_amd as moe
     c0 = synth.config_inputs(3)
