@@ -25,7 +25,6 @@ constexpr int FFN_BN = 128;   // columns per workgroup (bf16 path)
 constexpr int FFN_BK = 128;   // k chunk of the bf16 path, tiles of up to 64 rows
 constexpr int FFN_BK_TALL = 64;   // k chunk for tiles of 65..128 rows
 constexpr int FFN_GROUP = 8;             // row tiles per chunk of the grouped order
-constexpr int FFN_DENSE_MIN_ROWS = 64;   // a slot's last piece goes to the 256 x 256 tile kernel if longer than this
 
 struct __attribute__((aligned(16))) WorkItem {
     int expert, row_begin, row_end;
@@ -49,9 +48,10 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const bf16_t *__restr
 }
 
 // ------------------------------------------------------------------ work list
-// dense != 0 (slot schedule only): a slot's rows go, 256 at a time, to the list of the 256 x 256 tile
-// kernel (it skips the row blocks a shorter last piece does not have); only a last piece of at most
-// 64 rows, the weight-streaming case, stays with the 128-column kernel.
+// dense != 0 (slot schedule only): every slot's rows go, 256 at a time, to the list of the 256 x 256 tile
+// kernel (it skips the row blocks a shorter last piece does not have) and the 128-column kernel gets
+// nothing.  (Leaving it the last pieces of up to 64 rows, the weight-streaming case, was 3.5 % slower on
+// the extreme-skew workload: a second, HBM-bound launch after an MFMA-bound one instead of one mixed one.)
 // n_items = {row tiles, group size of the grouped order, dense tiles}.
 __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__restrict__ slot_offset,
                                                             const int32_t *__restrict__ slot_expert,
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(1024) void ffn_worklist_kernel(const int32_t *__res
             if (schedule == MOE_SCHEDULE_SLOTS) {
                 r1 = slot_offset[p + 1];
                 const int n = r1 > r0 ? r1 - r0 : 0;
-                if (dense) nd = n / DENSE_BM + (n % DENSE_BM > FFN_DENSE_MIN_ROWS ? 1 : 0);
+                if (dense) nd = (n + DENSE_BM - 1) / DENSE_BM;
                 const int covered = nd * DENSE_BM < n ? nd * DENSE_BM : n;
                 cnt = (n - covered + tile_rows - 1) / tile_rows;
                 reuse = cnt + nd > 1 || (p > 0 && slot_expert[p - 1] == e) || (p + 1 < P && slot_expert[p + 1] == e);
@@ -314,8 +314,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restri
 }
 
 static inline int ffn_max_items(int max_rows, int max_slots) { return max_slots + max_rows / FFN_BM + 1; }
-// every dense tile but the last of a slot has 256 rows, and that last one more than 64
-static inline int ffn_max_dense(int max_rows) { return max_rows / 64 + 1; }
+// every dense tile but the last of a slot has 256 rows
+static inline int ffn_max_dense(int max_rows, int max_slots) { return max_rows / DENSE_BM + max_slots + 1; }
 
 // The 256 x 256 tile pays off when slots are long: it is launched when the rows could fill slots of
 // 64 and more on average, the matrix sizes fit its tiling, and the batch can fill the chip.
@@ -367,7 +367,7 @@ extern "C" size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, in
     size_t esz = dtype == MOE_F32 ? 4 : 2;
     size_t h = align_up((size_t)(max_rows > 0 ? max_rows : 1) * F * esz, 256);
     size_t items = align_up((size_t)ffn_max_items(max_rows, max_slots) * sizeof(WorkItem), 256);
-    size_t dense = align_up((size_t)ffn_max_dense(max_rows) * sizeof(DenseTile), 256);
+    size_t dense = align_up((size_t)ffn_max_dense(max_rows, max_slots) * sizeof(DenseTile), 256);
     return h + items + dense + 256;
 }
 
@@ -416,7 +416,7 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
     int max_items = ffn_max_items(max_rows, max_slots);
     p += align_up((size_t)max_items * sizeof(WorkItem), 256);
     DenseTile *dtiles = (DenseTile *)p;
-    const int max_dense = ffn_max_dense(max_rows);
+    const int max_dense = ffn_max_dense(max_rows, max_slots);
     p += align_up((size_t)max_dense * sizeof(DenseTile), 256);
     int32_t *n_items = (int32_t *)p;
 
@@ -465,7 +465,9 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
                                n_items + 2, (bf16_t *)h);
             MOE_CHECK_LAUNCH("moe_expert_ffn/dense gemm1");
         }
-        if (tall)
+        if (dense) {
+            // the dense kernel took every row
+        } else if (tall)
             hipLaunchKernelGGL((ffn_gemm_bf16_kernel<true, true>), dim3(g1), dim3(GEMM_THREADS), 0, st,
                                (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, E, list,
                                n_items, slot_offset, slot_expert, n_slots, max_slots, schedule, max_rows,
@@ -483,7 +485,8 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
                                n_items + 2, (bf16_t *)y_perm);
             MOE_CHECK_LAUNCH("moe_expert_ffn/dense gemm2");
         }
-        if (tall)
+        if (dense) {
+        } else if (tall)
             hipLaunchKernelGGL((ffn_gemm_bf16_kernel<false, true>), dim3(g2), dim3(GEMM_THREADS), 0, st,
                                (const bf16_t *)h, (const int32_t *)nullptr, max_rows, (const bf16_t *)w2, F, d, E,
                                list, n_items, slot_offset, slot_expert, n_slots, max_slots, schedule, max_rows,
