@@ -8,9 +8,9 @@
 //             and the kernel walks its rows 64 at a time.
 //   gemm1     h = relu(x_perm * W1[e])   per (row tile, 128-column tile)
 //   gemm2     y_perm = h * W2[e]
-// At large batch a second list takes the stretches of more than 128 rows, 256 at a time; those run
-// on the compute-bound 256 x 256 tile (gemm_dense_bf16.h) in a launch of their own before the
-// 128-column kernel handles the rest.
+// At large batch the list cuts every slot into pieces of 256 rows instead and both products run on
+// the persistent 256 x 256 tile kernel (gemm_dense_bf16.h); the 128-column kernel is then not launched.
+// At small batch with short slots the 128-column kernel reads the slot tables itself (no list kernel).
 // Grids are sized for the worst case on the host (rows and slots are only known on the
 // device); workgroups beyond the list exit at once.  Workgroup ids are remapped so that the
 // column tiles of one row tile, which share the token rows, run on one XCD.
@@ -425,7 +425,7 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
                        ffn_use_dense(max_rows, max_slots, F, d, schedule);
     // Without the dense kernel (small batches, short slots on average, shapes outside its tiling, the
     // experts schedule) the 128-column kernel cuts work items 128 rows high and picks the tile height per
-    // item; with it, only pieces of at most 64 rows are left and the leaner build runs.
+    // item; with it, the 128-column kernel is not launched at all.
     const bool tall = dtype == MOE_BF16 && !dense;
     const int tile_rows = tall ? FFN_BM_TALL : FFN_BM;
     // Slots that hold 64 rows on average at most are one tile each, give or take: the 128-column kernel

@@ -241,8 +241,8 @@ def test_ffn_bf16_long_slots(schedule):
 
 def test_ffn_bf16_dense_tiles():
     """Enough rows that the 256 x 256 tile kernel takes the slots: lengths around its cut points
-    (a last piece of up to 64 rows stays with the 128-column kernel; 65.. rows use 3..8 row blocks of
-    the tile), short and empty slots beside them, and the fused gather."""
+    (pieces of 1..256 rows use 1..8 row blocks of the tile), short and empty slots beside them, and
+    the fused gather."""
     E, d, F = 7, 256, 512
     rows = [1500, 129, 0, 256, 257, 1, 385, 2000, 128, 513, 384, 64, 65, 96, 289, 320, 321, 32, 160, 224, 97]
     experts = [0, 0, 1, 1, 2, 2, 3, 3, 3, 4, 4, 4, 5, 5, 5, 5, 6, 6, 6, 6, 6]
