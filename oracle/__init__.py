@@ -63,6 +63,15 @@ def _chk(rc: int, what: str):
         raise ValueError(f"oracle {what}: invalid arguments")
 
 
+def _to_storage(a, st):
+    """float64 -> storage in one rounding (nearest, ties to even)."""
+    if st == 0:
+        return a.astype(np.float32)
+    m, e = np.frexp(a)                                  # bf16: 8 significant bits
+    r = np.ldexp(np.rint(np.ldexp(m, 8)), e - 8)        # exactly representable in binary32 and in bf16
+    return (r.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
 def route(x, w_router, b_router=None):
     """-> dict(idx int32[T], prob f32[T], logits f64[T,E], idx2 int32[T], margin f64[T])."""
     T, d = x.shape
@@ -119,13 +128,9 @@ def sru_attention(emb, w_cat, b_f, b_r, w_head, b_head=None):
     base = sru(emb, w_cat, b_f, b_r, w_head, b_head)
     B, L, _ = emb.shape
     st = _st(emb)
+
     def to_storage(a):
-        if st == 0:
-            return a.astype(np.float32)
-        # float64 -> bf16 in one rounding (nearest, ties to even): 8 significant bits
-        m, e = np.frexp(a)
-        r = np.ldexp(np.rint(np.ldexp(m, 8)), e - 8)        # exactly representable in binary32 and in bf16
-        return (r.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+        return _to_storage(a, st)
 
     z = sa.attend(base["h"], B, L, synth.storage_to_f64, to_storage)
     out = sa.head(z, w_head, b_head, synth.storage_to_f64)
@@ -207,4 +212,48 @@ def layer(x, w_router, b_router, w1, w2, C_, R, policy=0, plan_ids=None, residua
     dp = dispatch(x, rt["idx"], pl["replicas"], E, C_, E + R)
     y = ffn(dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"], pl["n_slots"], rows=rows)
     out = combine(y, x, dp["inv"], rt["prob"], residual)
+    return dict(route=rt, plan=pl, dispatch=dp, y_perm=y, out=out)
+
+
+def route_topk(x, w_router, b_router, k, renormalize=False):
+    """Top-k router (``oracle/topk.py`` states the reading): the logits of ``route`` and the k
+    largest of them per token.  -> dict(idx int32 [k,T], weight f32 [k,T], gap f64 [T], logits)."""
+    from . import topk
+    rt = route(x, w_router, b_router)
+    sel = topk.select(rt["logits"], k, renormalize)
+    return dict(idx=sel["idx"], weight=sel["weight"].astype(np.float32), gap=sel["gap"],
+                logits=rt["logits"])
+
+
+def combine_topk(y_perm, x, inv, weight, residual=0):
+    """inv int32 [k,T], weight f32 [k,T] -> out in the storage type of x (one rounding)."""
+    import synth
+    from . import topk
+    st = _st(x)
+    inv = np.ascontiguousarray(inv, np.int32)
+    out, passthrough = topk.combine(synth.storage_to_f64(y_perm), synth.storage_to_f64(x), inv,
+                                    np.asarray(weight, np.float32).astype(np.float64), bool(residual))
+    res = _to_storage(out, st)
+    res[passthrough] = x[passthrough]
+    return res
+
+
+def layer_topk(x, w_router, b_router, w1, w2, k, C_, R, policy=0, renormalize=False, residual=0,
+               idx=None, weight=None, rows=None):
+    """Whole top-k layer: route_topk -> plan / dispatch / expert FFN over the k*T assignments
+    (choice-major) -> combine_topk.  ``idx``/``weight`` [k,T] may be supplied to teacher-force the
+    routing decision.  -> dict with every intermediate."""
+    from . import topk
+    E = w_router.shape[1]
+    T = x.shape[0]
+    rt = route_topk(x, w_router, b_router, k, renormalize)
+    if idx is not None:
+        rt = dict(rt, idx=np.ascontiguousarray(idx, np.int32).reshape(k, T))
+    if weight is not None:
+        rt = dict(rt, weight=np.ascontiguousarray(weight, np.float32).reshape(k, T))
+    ids = rt["idx"].reshape(-1)
+    pl = plan(ids, E, R, C_, policy)
+    dp = dispatch(topk.assignment_rows(x, k), ids, pl["replicas"], E, C_, E + R)
+    y = ffn(dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"], pl["n_slots"], rows=rows)
+    out = combine_topk(y, x, dp["inv"].reshape(k, T), rt["weight"], residual)
     return dict(route=rt, plan=pl, dispatch=dp, y_perm=y, out=out)
