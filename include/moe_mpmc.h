@@ -43,6 +43,7 @@ extern "C" {
 #define MOE_BF16 1
 
 #define MOE_MAX_EXPERTS 1024 /* E  <= 1024 */
+#define MOE_MAX_TOPK 8       /* k  <= 8 (top-k routing) */
 #define MOE_MAX_SLOTS 4096   /* E + replica budget <= 4096 */
 
 #define MOE_LAYOUT_PLAIN 0  /* [E, K, N] row-major                                        */
@@ -71,6 +72,45 @@ size_t moe_route_workspace_bytes(int T, int d, int E, int dtype);
 int moe_route(const void *x, const void *w_router, int w_layout, const float *b_router, int T, int d,
               int E, int dtype, int32_t *expert_idx, float *expert_prob, float *logits_opt, void *ws,
               size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Top-k routing (Experiments, setup: one of the two tasks is run with top-3 routing).  The paper
+ * names the setting only; the reading built here is the usual one for a softmax gate:
+ *   choice j = 0..k-1 of token s: the expert with the j-th largest logit (lower id first among
+ *   equal logits); its weight is softmax(logit[s])[e_j], divided by the sum of the k weights when
+ *   renormalize = 1;  an assignment is numbered a = j*T + s (all first choices before all second
+ *   choices, which is also their priority under the capacity limit).
+ * moe_route_topk: expert_idx and expert_weight hold k*T entries in that order (entry j*T + s);
+ *   k = 1 gives moe_route's results bit for bit.  1 <= k <= min(MOE_MAX_TOPK, E).  Everything
+ *   else as moe_route (same workspace size).
+ * replica_plan takes the k*T ids as its batch.
+ * moe_dispatch_topk: moe_dispatch over the k*T assignments (expert_idx, perm, inv hold k*T
+ *   entries; workspace of moe_dispatch_workspace_bytes(k*T, E)); x still has T rows:
+ *   x_perm[inv[a]] = x[a mod T], and row_token[r] = perm[r] mod T for r < K, -1 for K <= r < k*T
+ *   (the row table moe_expert_ffn_rows gathers through).  x and x_perm may both be NULL.
+ * moe_expert_ffn_rows: moe_expert_ffn with a gather (row_index required) from a matrix of
+ *   n_x_rows rows, which need not equal max_rows; an index outside [0, n_x_rows) is never
+ *   dereferenced.  Workspace as moe_expert_ffn.
+ * moe_combine_topk: inv and expert_weight hold k*T entries;
+ *   out[s] = (residual ? x[s] : 0) + sum over j with inv[j*T+s] >= 0, in the order j = 0..k-1, of
+ *            expert_weight[j*T+s] * y_perm[inv[j*T+s]]   (binary32 multiply-adds, rounded once);
+ *   a token with no kept choice: out[s] = x[s] bit for bit.  k = 1 is moe_combine.
+ */
+int moe_route_topk(const void *x, const void *w_router, int w_layout, const float *b_router, int T,
+                   int d, int E, int dtype, int k, int renormalize, int32_t *expert_idx,
+                   float *expert_weight, float *logits_opt, void *ws, size_t ws_bytes, void *stream);
+int moe_dispatch_topk(const void *x, const int32_t *expert_idx, const int32_t *replicas, int T, int k,
+                      int d, int E, int slot_capacity, int max_slots, int dtype, int32_t *counts,
+                      int32_t *kept, int32_t *expert_offset, int32_t *slot_offset, int32_t *perm,
+                      int32_t *inv, int32_t *row_token, void *x_perm, void *ws, size_t ws_bytes,
+                      void *stream);
+int moe_expert_ffn_rows(const void *x, int n_x_rows, const int32_t *row_index, const void *w1,
+                        const void *w2, int weight_layout, const int32_t *slot_offset,
+                        const int32_t *slot_expert, const int32_t *n_slots, int max_rows, int max_slots,
+                        int E, int d, int F, int dtype, int schedule, void *y_perm, void *ws,
+                        size_t ws_bytes, void *stream);
+int moe_combine_topk(const void *y_perm, const void *x, const int32_t *inv, const float *expert_weight,
+                     int T, int k, int d, int dtype, int residual, void *out, void *stream);
 
 /* ---------------------------------------------------------------------------------------
  * sru_predict -- the expert predictor h_l of Algorithm 2 ("Expert k <- h_l(X_i[s])"): a stack

@@ -27,6 +27,7 @@ EXPORTS = (
     "moe_packed_weights_bytes", "moe_pack_weights",
     "moe_expert_ffn_workspace_bytes", "moe_expert_ffn", "moe_expert_ffn_set_timing_events",
     "moe_combine",
+    "moe_route_topk", "moe_dispatch_topk", "moe_expert_ffn_rows", "moe_combine_topk",
 )
 
 
@@ -73,6 +74,10 @@ def lib():
         _lib.moe_expert_ffn.argtypes = [P, P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P]
         _lib.moe_expert_ffn_set_timing_events.argtypes = [P, P, P]
         _lib.moe_combine.argtypes = [P, P, P, P, I, I, I, I, P, P]
+        _lib.moe_route_topk.argtypes = [P, P, I, P, I, I, I, I, I, I, P, P, P, P, S, P]
+        _lib.moe_dispatch_topk.argtypes = [P, P, P, I, I, I, I, I, I, I, P, P, P, P, P, P, P, P, P, S, P]
+        _lib.moe_expert_ffn_rows.argtypes = [P, I, P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P]
+        _lib.moe_combine_topk.argtypes = [P, P, P, P, I, I, I, I, I, P, P]
     return _lib
 
 
@@ -243,6 +248,116 @@ def moe_combine(y_perm, x, inv, expert_prob, residual=0, out=None):
     _check(lib().moe_combine(_ptr(y_perm), _ptr(x), _ptr(inv), _ptr(expert_prob), T, d, _dt(x), int(residual),
                              _ptr(o), _stream()))
     return o
+
+
+# --------------------------------------------------------------------------- top-k routing
+def moe_route_topk(x, w_router, b_router, k, renormalize=False, want_logits=False, out=None, ws=None,
+                   w_layout=LAYOUT_PLAIN):
+    """-> (expert_idx int32[k,T], expert_weight f32[k,T], logits f32[T,E] or None); choice-major."""
+    T, d = x.shape
+    E = w_router.shape[1]
+    dev = x.device
+    dt = _dt(x)
+    assert _dt(w_router) == dt and w_router.shape[0] == d
+    idx, wgt = out if out is not None else (_i32(k * T, dev).view(k, T),
+                                            torch.empty(k, T, dtype=torch.float32, device=dev))
+    logits = torch.empty(T, E, dtype=torch.float32, device=dev) if want_logits else None
+    ws = ws if ws is not None else _ws(lib().moe_route_workspace_bytes(T, d, E, dt), dev)
+    _check(lib().moe_route_topk(_ptr(x), _ptr(w_router), w_layout, _ptr(b_router), T, d, E, dt, int(k),
+                                int(bool(renormalize)), _ptr(idx), _ptr(wgt), _ptr(logits), _ptr(ws), ws.numel(),
+                                _stream()))
+    return idx, wgt, logits
+
+
+def moe_dispatch_topk(x, expert_idx, replicas, E, slot_capacity, max_slots, out=None, ws=None, shape=None,
+                      dtype=None):
+    """expert_idx int32[k,T] -> dict(counts, kept, expert_offset, slot_offset, perm[k*T], inv[k,T],
+    row_token[k*T], x_perm [k*T,d] or None).  With x=None (give ``shape=(T, d)`` and ``dtype``) only
+    the index tables are built."""
+    k = expert_idx.shape[0]
+    T, d = x.shape if x is not None else shape
+    A = k * T
+    dev = expert_idx.device
+    dt = _dt(x) if x is not None else (MOE_BF16 if dtype == torch.bfloat16 else MOE_F32)
+    o = out if out is not None else dict(
+        counts=_i32(E, dev), kept=_i32(E, dev), expert_offset=_i32(E + 1, dev), slot_offset=_i32(max_slots + 1, dev),
+        perm=_i32(A, dev), inv=_i32(A, dev).view(k, T), row_token=_i32(A, dev),
+        x_perm=torch.empty(A, d, dtype=x.dtype, device=dev) if x is not None else None)
+    ws = ws if ws is not None else _ws(lib().moe_dispatch_workspace_bytes(A, E), dev)
+    xp = o["x_perm"] if x is not None else None
+    _check(lib().moe_dispatch_topk(_ptr(x), _ptr(expert_idx), _ptr(replicas), T, k, d, E, slot_capacity, max_slots,
+                                   dt, _ptr(o["counts"]), _ptr(o["kept"]), _ptr(o["expert_offset"]),
+                                   _ptr(o["slot_offset"]), _ptr(o["perm"]), _ptr(o["inv"]), _ptr(o["row_token"]),
+                                   _ptr(xp), _ptr(ws), ws.numel(), _stream()))
+    return o
+
+
+def moe_expert_ffn_rows(x, row_index, max_rows, w1, w2, slot_offset, slot_expert, n_slots, E, F, max_slots=None,
+                        schedule=SCHEDULE_SLOTS, weight_layout=None, out=None, ws=None):
+    """moe_expert_ffn gathering its rows from x [n_x_rows, d] through row_index [max_rows]
+    (moe_dispatch_topk's row_token).  -> y_perm [max_rows, d]."""
+    n_x_rows, d = x.shape
+    dev = x.device
+    dt = _dt(x)
+    if weight_layout is None:
+        weight_layout = LAYOUT_PACKED if dt == MOE_BF16 else LAYOUT_PLAIN
+    if max_slots is None:
+        max_slots = slot_expert.shape[0]
+    y = out if out is not None else torch.empty(max_rows, d, dtype=x.dtype, device=dev)
+    ws = ws if ws is not None else _ws(lib().moe_expert_ffn_workspace_bytes(max_rows, max_slots, d, F, dt), dev)
+    _check(lib().moe_expert_ffn_rows(_ptr(x), n_x_rows, _ptr(row_index), _ptr(w1), _ptr(w2), weight_layout,
+                                     _ptr(slot_offset), _ptr(slot_expert), _ptr(n_slots), max_rows, max_slots, E, d,
+                                     F, dt, schedule, _ptr(y), _ptr(ws), ws.numel(), _stream()))
+    return y
+
+
+def moe_combine_topk(y_perm, x, inv, expert_weight, residual=0, out=None):
+    """inv int32[k,T], expert_weight f32[k,T] -> out [T,d]."""
+    T, d = x.shape
+    k = inv.shape[0]
+    o = out if out is not None else torch.empty_like(x)
+    _check(lib().moe_combine_topk(_ptr(y_perm), _ptr(x), _ptr(inv), _ptr(expert_weight), T, k, d, _dt(x),
+                                  int(residual), _ptr(o), _stream()))
+    return o
+
+
+class MoeLayerTopK:
+    """The top-k layer: route_topk -> plan over the k*T ids -> dispatch_topk -> expert FFN (rows
+    gathered through row_token) -> combine_topk.  Preallocated buffers, pure sequencing."""
+
+    def __init__(self, T, d, F, E, k, budget, slot_capacity, dtype, device="cuda", policy=0, renormalize=False):
+        self.T, self.d, self.F, self.E, self.k, self.R, self.C = T, d, F, E, k, budget, slot_capacity
+        self.policy, self.renormalize = policy, renormalize
+        self.max_slots = E + budget
+        A = k * T
+        dev = torch.device(device)
+        dt = MOE_BF16 if dtype == torch.bfloat16 else MOE_F32
+        L = lib()
+        self.route_out = (_i32(A, dev).view(k, T), torch.empty(k, T, dtype=torch.float32, device=dev))
+        self.route_ws = _ws(L.moe_route_workspace_bytes(T, d, E, dt), dev)
+        self.plan_out = dict(plan_counts=_i32(E, dev), replicas=_i32(E, dev), slot_base=_i32(E + 1, dev),
+                             slot_expert=_i32(E + budget, dev), n_slots=_i32(1, dev))
+        self.plan_ws = _ws(L.replica_plan_workspace_bytes(A, E), dev)
+        self.disp_out = dict(counts=_i32(E, dev), kept=_i32(E, dev), expert_offset=_i32(E + 1, dev),
+                             slot_offset=_i32(self.max_slots + 1, dev), perm=_i32(A, dev),
+                             inv=_i32(A, dev).view(k, T), row_token=_i32(A, dev), x_perm=None)
+        self.disp_ws = _ws(L.moe_dispatch_workspace_bytes(A, E), dev)
+        self.y_perm = torch.zeros(A, d, dtype=dtype, device=dev)
+        self.ffn_ws = _ws(L.moe_expert_ffn_workspace_bytes(A, self.max_slots, d, F, dt), dev)
+        self.out = torch.empty(T, d, dtype=dtype, device=dev)
+
+    def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
+                out=None, router_layout=LAYOUT_PLAIN):
+        idx, wgt, _ = moe_route_topk(x, w_router, b_router, self.k, self.renormalize, out=self.route_out,
+                                     ws=self.route_ws, w_layout=router_layout)
+        pl = replica_plan(idx.view(-1) if plan_ids is None else plan_ids, self.E, self.R, self.C, self.policy,
+                          out=self.plan_out, ws=self.plan_ws)
+        dp = moe_dispatch_topk(None, idx, pl["replicas"], self.E, self.C, self.max_slots, out=self.disp_out,
+                               ws=self.disp_ws, shape=(self.T, self.d), dtype=x.dtype)
+        y = moe_expert_ffn_rows(x, dp["row_token"], self.k * self.T, w1, w2, dp["slot_offset"], pl["slot_expert"],
+                                pl["n_slots"], self.E, self.F, max_slots=self.max_slots, schedule=schedule,
+                                out=self.y_perm, ws=self.ffn_ws)
+        return moe_combine_topk(y, x, dp["inv"], wgt, residual, out=self.out if out is None else out)
 
 
 # --------------------------------------------------------------------------- whole layer

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
     const int32_t *__restrict__ idx, const int32_t *__restrict__ replicas, int T, int E, int nbits, int C, int nb,
     int max_slots, const int32_t *__restrict__ block_hist, int32_t *__restrict__ counts, int32_t *__restrict__ kept,
     int32_t *__restrict__ expert_offset, int32_t *__restrict__ slot_offset, int32_t *__restrict__ perm,
-    int32_t *__restrict__ inv)
+    int32_t *__restrict__ inv, int n_tokens, int32_t *__restrict__ row_token)
 {
     __shared__ unsigned short chunk_cnt[DSP_CHUNKS][MOE_MAX_EXPERTS];
     __shared__ int before_e[MOE_MAX_EXPERTS];   // tokens of e in earlier blocks
@@ -189,6 +189,10 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
             inv[t] = dest;
             if (dest >= 0) perm[dest] = t;
             if (t >= K) perm[t] = -1;
+            if (row_token) {        // top-k: entry t is assignment (t / n_tokens, t % n_tokens)
+                if (dest >= 0) row_token[dest] = t % n_tokens;
+                if (t >= K) row_token[t] = -1;
+            }
         }
     }
 }
@@ -200,12 +204,15 @@ constexpr int GATHER_ROWS = DSP_THREADS / 32;
 __global__ __launch_bounds__(DSP_THREADS) void dispatch_gather_kernel(const uint4 *__restrict__ x,
                                                                       const int32_t *__restrict__ perm,
                                                                       const int32_t *__restrict__ expert_offset, int E,
-                                                                      int vec_per_row, uint4 *__restrict__ x_perm)
+                                                                      int n_tokens, int vec_per_row,
+                                                                      uint4 *__restrict__ x_perm)
 {
     const int pos = blockIdx.x * GATHER_ROWS + (threadIdx.x >> 5);
     const int l = threadIdx.x & 31;
     if (pos >= expert_offset[E]) return;
-    const uint4 *src = x + (size_t)perm[pos] * vec_per_row;
+    int row = perm[pos];
+    if (row >= n_tokens) row %= n_tokens;     // top-k: assignment -> its token
+    const uint4 *src = x + (size_t)row * vec_per_row;
     uint4 *dst = x_perm + (size_t)pos * vec_per_row;
     int c = l;
     for (; c + 96 < vec_per_row; c += 128) {
@@ -235,52 +242,73 @@ extern "C" size_t moe_dispatch_workspace_bytes(int T, int E)
     return align_up((nb > 0 ? nb : 1) * (size_t)E * sizeof(int32_t), 256);
 }
 
-extern "C" int moe_dispatch(const void *x, const int32_t *expert_idx, const int32_t *replicas, int T, int d,
-                            int E, int slot_capacity, int max_slots, int dtype, int32_t *counts,
-                            int32_t *kept, int32_t *expert_offset, int32_t *slot_offset, int32_t *perm,
-                            int32_t *inv, void *x_perm, void *ws, size_t ws_bytes, void *stream)
+// T entries (tokens, or k*n_tokens assignments of a top-k layer) over the rows of n_tokens tokens
+static int dispatch_checked(const char *who, const void *x, const int32_t *expert_idx, const int32_t *replicas, int T,
+                            int n_tokens, int d, int E, int slot_capacity, int max_slots, int dtype, int32_t *counts,
+                            int32_t *kept, int32_t *expert_offset, int32_t *slot_offset, int32_t *perm, int32_t *inv,
+                            int32_t *row_token, void *x_perm, void *ws, size_t ws_bytes, void *stream)
 {
     MOE_REQUIRE(T >= 0 && d > 0 && E > 0 && slot_capacity >= 1 && max_slots >= 0, MOE_ERR_INVALID_ARG,
-                "moe_dispatch: T=%d d=%d E=%d slot_capacity=%d max_slots=%d out of range", T, d, E,
-                slot_capacity, max_slots);
-    MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_INVALID_ARG, "moe_dispatch: unknown dtype %d",
-                dtype);
-    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_dispatch: E=%d exceeds %d", E,
-                MOE_MAX_EXPERTS);
-    MOE_REQUIRE(counts && kept && expert_offset && (T == 0 || (expert_idx && perm && inv)),
-                MOE_ERR_INVALID_ARG, "moe_dispatch: null output or id pointer");
+                "%s: T=%d d=%d E=%d slot_capacity=%d max_slots=%d out of range", who, T, d, E, slot_capacity,
+                max_slots);
+    MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, dtype);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "%s: E=%d exceeds %d", who, E, MOE_MAX_EXPERTS);
+    MOE_REQUIRE(counts && kept && expert_offset && (T == 0 || (expert_idx && perm && inv)), MOE_ERR_INVALID_ARG,
+                "%s: null output or id pointer", who);
     MOE_REQUIRE((x == nullptr) == (x_perm == nullptr), MOE_ERR_INVALID_ARG,
-                "moe_dispatch: x and x_perm must both be given or both be NULL");
-    MOE_REQUIRE(!slot_offset || max_slots >= E, MOE_ERR_INVALID_ARG,
-                "moe_dispatch: max_slots=%d smaller than E=%d", max_slots, E);
+                "%s: x and x_perm must both be given or both be NULL", who);
+    MOE_REQUIRE(!slot_offset || max_slots >= E, MOE_ERR_INVALID_ARG, "%s: max_slots=%d smaller than E=%d", who,
+                max_slots, E);
     size_t esz = dtype == MOE_F32 ? 4 : 2;
-    MOE_REQUIRE(((size_t)d * esz) % 16 == 0, MOE_ERR_INVALID_ARG,
-                "moe_dispatch: row size %zu bytes is not a multiple of 16", (size_t)d * esz);
-    MOE_REQUIRE(aligned16(x) && aligned16(x_perm), MOE_ERR_INVALID_ARG, "moe_dispatch: x / x_perm misaligned");
+    MOE_REQUIRE(((size_t)d * esz) % 16 == 0, MOE_ERR_INVALID_ARG, "%s: row size %zu bytes is not a multiple of 16",
+                who, (size_t)d * esz);
+    MOE_REQUIRE(aligned16(x) && aligned16(x_perm), MOE_ERR_INVALID_ARG, "%s: x / x_perm misaligned", who);
     MOE_REQUIRE(ws && ws_bytes >= moe_dispatch_workspace_bytes(T, E), MOE_ERR_WORKSPACE,
-                "moe_dispatch: workspace of %zu bytes needed, %zu given", moe_dispatch_workspace_bytes(T, E),
-                ws_bytes);
+                "%s: workspace of %zu bytes needed, %zu given", who, moe_dispatch_workspace_bytes(T, E), ws_bytes);
     hipStream_t st = (hipStream_t)stream;
     int nb = ceil_div(T, DSP_TOKENS);
     int32_t *block_hist = (int32_t *)ws;
     if (nb > 0) {
         hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nb), dim3(DSP_THREADS), 0, st, expert_idx, T, E, block_hist);
-        MOE_CHECK_LAUNCH("moe_dispatch/hist");
+        MOE_CHECK_LAUNCH(who);
     }
     {
         int nbits = 0;
         while ((1 << nbits) < E) ++nbits;
         hipLaunchKernelGGL(dispatch_permute_kernel, dim3(nb > 0 ? nb : 1), dim3(DSP_THREADS), 0, st, expert_idx,
                            replicas, T, E, nbits, slot_capacity, nb, max_slots, block_hist, counts, kept,
-                           expert_offset, slot_offset, perm, inv);
-        MOE_CHECK_LAUNCH("moe_dispatch/permute");
+                           expert_offset, slot_offset, perm, inv, n_tokens > 0 ? n_tokens : 1, row_token);
+        MOE_CHECK_LAUNCH(who);
         if (x && nb > 0) {
             int vec_per_row = (int)((size_t)d * esz / 16);
             int grid = ceil_div(T, GATHER_ROWS);
             hipLaunchKernelGGL(dispatch_gather_kernel, dim3(grid), dim3(DSP_THREADS), 0, st, (const uint4 *)x, perm,
-                               expert_offset, E, vec_per_row, (uint4 *)x_perm);
-            MOE_CHECK_LAUNCH("moe_dispatch/gather");
+                               expert_offset, E, n_tokens, vec_per_row, (uint4 *)x_perm);
+            MOE_CHECK_LAUNCH(who);
         }
     }
     return MOE_OK;
+}
+
+extern "C" int moe_dispatch(const void *x, const int32_t *expert_idx, const int32_t *replicas, int T, int d,
+                            int E, int slot_capacity, int max_slots, int dtype, int32_t *counts,
+                            int32_t *kept, int32_t *expert_offset, int32_t *slot_offset, int32_t *perm,
+                            int32_t *inv, void *x_perm, void *ws, size_t ws_bytes, void *stream)
+{
+    return dispatch_checked("moe_dispatch", x, expert_idx, replicas, T, T, d, E, slot_capacity, max_slots, dtype,
+                            counts, kept, expert_offset, slot_offset, perm, inv, nullptr, x_perm, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_dispatch_topk(const void *x, const int32_t *expert_idx, const int32_t *replicas, int T, int k,
+                                 int d, int E, int slot_capacity, int max_slots, int dtype, int32_t *counts,
+                                 int32_t *kept, int32_t *expert_offset, int32_t *slot_offset, int32_t *perm,
+                                 int32_t *inv, int32_t *row_token, void *x_perm, void *ws, size_t ws_bytes,
+                                 void *stream)
+{
+    MOE_REQUIRE(T >= 0 && k >= 1 && k <= MOE_MAX_TOPK && (long long)T * k <= 0x7fffffffLL, MOE_ERR_INVALID_ARG,
+                "moe_dispatch_topk: T=%d k=%d out of range (k <= %d, T*k < 2^31)", T, k, MOE_MAX_TOPK);
+    MOE_REQUIRE(T == 0 || row_token, MOE_ERR_INVALID_ARG, "moe_dispatch_topk: null row_token");
+    return dispatch_checked("moe_dispatch_topk", x, expert_idx, replicas, T * k, T, d, E, slot_capacity, max_slots,
+                            dtype, counts, kept, expert_offset, slot_offset, perm, inv, row_token, x_perm, ws, ws_bytes,
+                            stream);
 }

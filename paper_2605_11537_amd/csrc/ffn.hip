@@ -249,7 +249,8 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void ffn_gemm_bf16_kernel(
 // 64x64 tile, 256 threads, 4x4 outputs per thread, k ascending.
 template <bool RELU>
 __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ W,
-                                                           const int32_t *__restrict__ row_index, int K, int N, int E,
+                                                           const int32_t *__restrict__ row_index, int n_src_rows,
+                                                           int K, int N, int E,
                                                            const WorkItem *__restrict__ items,
                                                            const int32_t *__restrict__ n_items, int max_rows,
                                                            float *__restrict__ C)
@@ -273,7 +274,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restri
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (r < nrows) {
                     int src = row_index ? row_index[r0 + r] : r0 + r;
-                    if (src >= 0 && src < max_rows) v = *reinterpret_cast<const float4 *>(A + (size_t)src * K + k0 + kq);
+                    if (src >= 0 && src < n_src_rows) v = *reinterpret_cast<const float4 *>(A + (size_t)src * K + k0 + kq);
                 }
                 As[kq + 0][r] = v.x;
                 As[kq + 1][r] = v.y;
@@ -371,11 +372,13 @@ extern "C" size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, in
     return h + items + dense + 256;
 }
 
-extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, const void *w1, const void *w2,
-                              int weight_layout,
-                              const int32_t *slot_offset, const int32_t *slot_expert, const int32_t *n_slots,
-                              int max_rows, int max_slots, int E, int d, int F, int dtype, int schedule,
-                              void *y_perm, void *ws, size_t ws_bytes, void *stream)
+// n_x_rows: rows of the matrix x_perm points to -- max_rows, or with row_index any number (the
+// indices are checked against it)
+static int expert_ffn_checked(const void *x_perm, int n_x_rows, const int32_t *row_index, const void *w1,
+                              const void *w2, int weight_layout, const int32_t *slot_offset,
+                              const int32_t *slot_expert, const int32_t *n_slots, int max_rows, int max_slots, int E,
+                              int d, int F, int dtype, int schedule, void *y_perm, void *ws, size_t ws_bytes,
+                              void *stream)
 {
     MOE_REQUIRE(max_rows >= 0 && max_slots > 0 && E > 0 && d > 0 && F > 0, MOE_ERR_INVALID_ARG,
                 "moe_expert_ffn: max_rows=%d max_slots=%d E=%d d=%d F=%d out of range", max_rows, max_slots, E, d,
@@ -461,7 +464,7 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
                         MOE_ERR_HIP, "moe_expert_ffn: cannot read the compute unit count");
             n_cu -= n_cu % 8;   // one persistent workgroup per CU, the same number on every XCD
             hipLaunchKernelGGL(ffn_dense_bf16_kernel<true>, dim3(n_cu), dim3(GEMM_THREADS), 0, st,
-                               (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, dtiles,
+                               (const bf16_t *)x_perm, row_index, n_x_rows, (const bf16_t *)w1, d, F, dtiles,
                                n_items + 2, (bf16_t *)h);
             MOE_CHECK_LAUNCH("moe_expert_ffn/dense gemm1");
         }
@@ -469,12 +472,12 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
             // the dense kernel took every row
         } else if (tall)
             hipLaunchKernelGGL((ffn_gemm_bf16_kernel<true, true>), dim3(g1), dim3(GEMM_THREADS), 0, st,
-                               (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, E, list,
+                               (const bf16_t *)x_perm, row_index, n_x_rows, (const bf16_t *)w1, d, F, E, list,
                                n_items, slot_offset, slot_expert, n_slots, max_slots, schedule, max_rows,
                                (bf16_t *)h);
         else
             hipLaunchKernelGGL((ffn_gemm_bf16_kernel<true, false>), dim3(g1), dim3(GEMM_THREADS), 0,
-                               st, (const bf16_t *)x_perm, row_index, max_rows, (const bf16_t *)w1, d, F, E, list,
+                               st, (const bf16_t *)x_perm, row_index, n_x_rows, (const bf16_t *)w1, d, F, E, list,
                                n_items, slot_offset, slot_expert, n_slots, max_slots, schedule, max_rows,
                                (bf16_t *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
@@ -500,14 +503,36 @@ extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, cons
     } else {
         int g1 = grid_items * (F / 64), g2 = grid_items * (d / 64);
         hipLaunchKernelGGL(ffn_gemm_f32_kernel<true>, dim3(g1), dim3(256), 0, st, (const float *)x_perm,
-                           (const float *)w1, row_index, d, F, E, items, n_items, max_rows, (float *)h);
+                           (const float *)w1, row_index, n_x_rows, d, F, E, items, n_items, max_rows, (float *)h);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm1");
         if (ev[1]) (void)hipEventRecord(ev[1], st);
         hipLaunchKernelGGL(ffn_gemm_f32_kernel<false>, dim3(g2), dim3(256), 0, st, (const float *)h,
-                           (const float *)w2, (const int32_t *)nullptr, F, d, E, items, n_items, max_rows,
+                           (const float *)w2, (const int32_t *)nullptr, max_rows, F, d, E, items, n_items, max_rows,
                            (float *)y_perm);
         MOE_CHECK_LAUNCH("moe_expert_ffn/gemm2");
     }
     if (ev[2]) (void)hipEventRecord(ev[2], st);
     return MOE_OK;
+}
+
+extern "C" int moe_expert_ffn(const void *x_perm, const int32_t *row_index, const void *w1, const void *w2,
+                              int weight_layout,
+                              const int32_t *slot_offset, const int32_t *slot_expert, const int32_t *n_slots,
+                              int max_rows, int max_slots, int E, int d, int F, int dtype, int schedule,
+                              void *y_perm, void *ws, size_t ws_bytes, void *stream)
+{
+    return expert_ffn_checked(x_perm, max_rows, row_index, w1, w2, weight_layout, slot_offset, slot_expert, n_slots,
+                              max_rows, max_slots, E, d, F, dtype, schedule, y_perm, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_expert_ffn_rows(const void *x, int n_x_rows, const int32_t *row_index, const void *w1,
+                                   const void *w2, int weight_layout, const int32_t *slot_offset,
+                                   const int32_t *slot_expert, const int32_t *n_slots, int max_rows, int max_slots,
+                                   int E, int d, int F, int dtype, int schedule, void *y_perm, void *ws,
+                                   size_t ws_bytes, void *stream)
+{
+    MOE_REQUIRE(n_x_rows >= 0 && (max_rows == 0 || (row_index && n_x_rows > 0)), MOE_ERR_INVALID_ARG,
+                "moe_expert_ffn_rows: n_x_rows=%d out of range or null row_index", n_x_rows);
+    return expert_ffn_checked(x, n_x_rows, row_index, w1, w2, weight_layout, slot_offset, slot_expert, n_slots,
+                              max_rows, max_slots, E, d, F, dtype, schedule, y_perm, ws, ws_bytes, stream);
 }

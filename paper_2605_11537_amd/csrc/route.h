@@ -6,7 +6,8 @@
 namespace moe {
 size_t route_ws_bytes(int d, int E, int dtype);
 int route_launch(const void *x, const void *w_router, int w_layout, const float *b_router, int T, int d, int E,
-                 int dtype, int32_t *idx, float *prob, float *logits_opt, void *ws, hipStream_t st, const char *who);
+                 int dtype, int top_k, int renormalize, int32_t *idx, float *prob, float *logits_opt, void *ws,
+                 hipStream_t st, const char *who);
 // in [K][N] bf16 row-major -> packed image (N a multiple of 32), 16-byte piece ((n/32)*(K/8) + k/8)*32 + n%32
 int pack_matrix_launch(const void *in, int K, int N, void *out, hipStream_t st, const char *who);
 // attention.hip: z = h + sparsemax-attention context over each of the B sequences of L states (bf16, n features)

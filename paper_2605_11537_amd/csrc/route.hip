@@ -44,6 +44,7 @@ template <int NB, int MB>
 __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *__restrict__ x,
                                                                   const bf16_t *__restrict__ wr_packed,
                                                                   const float *__restrict__ bias, int T, int d,
+                                                                  int top_k, int renormalize,
                                                                   int32_t *__restrict__ idx, float *__restrict__ prob,
                                                                   float *__restrict__ logits_opt)
 {
@@ -92,9 +93,49 @@ __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *
 #pragma unroll
         for (int o = 1; o < 8; o <<= 1) z += __shfl_xor(z, o, 64);
         const int grow = row0 + mb * 32 + r;
-        if (sub == 0 && mb * 32 + r < nrows) {
-            idx[grow] = bi;
-            prob[grow] = 1.f / z;
+        if (top_k == 1) {
+            if (sub == 0 && mb * 32 + r < nrows) {
+                idx[grow] = bi;
+                prob[grow] = 1.f / z;
+            }
+        } else {
+            // choice j: the largest logit after choice j-1 in the order (logit descending, id ascending)
+            int ci[MOE_MAX_TOPK];
+            float cw[MOE_MAX_TOPK];
+            ci[0] = bi;
+            cw[0] = 1.f / z;
+            float pv = best, wsum = cw[0];
+            int pi = bi;
+#pragma unroll
+            for (int j = 1; j < MOE_MAX_TOPK; ++j) {
+                if (j < top_k) {
+                    float v = -INFINITY;
+                    int vi = 0x7fffffff;
+                    for (int c = sub; c < E; c += 8) {
+                        const float t = row[c];
+                        if (t < pv || (t == pv && c > pi)) argmax_merge(v, vi, t, c);
+                    }
+#pragma unroll
+                    for (int o = 1; o < 8; o <<= 1) {
+                        float ov = __shfl_xor(v, o, 64);
+                        int oi = __shfl_xor(vi, o, 64);
+                        argmax_merge(v, vi, ov, oi);
+                    }
+                    ci[j] = vi;
+                    cw[j] = expf(v - best) / z;
+                    wsum += cw[j];
+                    pv = v;
+                    pi = vi;
+                }
+            }
+            if (sub == 0 && mb * 32 + r < nrows) {
+#pragma unroll
+                for (int j = 0; j < MOE_MAX_TOPK; ++j)
+                    if (j < top_k) {
+                        idx[(size_t)j * T + grow] = ci[j];
+                        prob[(size_t)j * T + grow] = renormalize ? cw[j] / wsum : cw[j];
+                    }
+            }
         }
         if (logits_opt) {
             for (int i = tid; i < 32 * E; i += GEMM_THREADS) {
@@ -110,6 +151,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *
 template <bool BF16>
 __global__ __launch_bounds__(256) void route_generic_kernel(const void *__restrict__ xv, const void *__restrict__ wv,
                                                             const float *__restrict__ bias, int T, int d, int E,
+                                                            int top_k, int renormalize,
                                                             int32_t *__restrict__ idx, float *__restrict__ prob,
                                                             float *__restrict__ logits_opt)
 {
@@ -152,9 +194,49 @@ __global__ __launch_bounds__(256) void route_generic_kernel(const void *__restri
         if (lane + i * WAVE < E) z += expf(l[i] - best);
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) z += __shfl_xor(z, o, 64);
+    if (top_k == 1) {
+        if (lane == 0) {
+            idx[s] = bi;
+            prob[s] = 1.f / z;
+        }
+        return;
+    }
+    int ci[MOE_MAX_TOPK];
+    float cw[MOE_MAX_TOPK];
+    ci[0] = bi;
+    cw[0] = 1.f / z;
+    float pv = best, wsum = cw[0];
+    int pi = bi;
+#pragma unroll
+    for (int j = 1; j < MOE_MAX_TOPK; ++j) {
+        if (j < top_k) {
+            float v = -INFINITY;
+            int vi = 0x7fffffff;
+#pragma unroll
+            for (int i = 0; i < PER; ++i) {
+                const int e = lane + i * WAVE;
+                if (e < E && (l[i] < pv || (l[i] == pv && e > pi))) argmax_merge(v, vi, l[i], e);
+            }
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                float ov = __shfl_xor(v, o, 64);
+                int oi = __shfl_xor(vi, o, 64);
+                argmax_merge(v, vi, ov, oi);
+            }
+            ci[j] = vi;
+            cw[j] = expf(v - best) / z;
+            wsum += cw[j];
+            pv = v;
+            pi = vi;
+        }
+    }
     if (lane == 0) {
-        idx[s] = bi;
-        prob[s] = 1.f / z;
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_TOPK; ++j)
+            if (j < top_k) {
+                idx[(size_t)j * T + s] = ci[j];
+                prob[(size_t)j * T + s] = renormalize ? cw[j] / wsum : cw[j];
+            }
     }
 }
 
@@ -174,7 +256,8 @@ int pack_matrix_launch(const void *in, int K, int N, void *out, hipStream_t st, 
 
 // shared with sru_predict (its head is the same product + argmax)
 int route_launch(const void *x, const void *w_router, int w_layout, const float *b_router, int T, int d, int E,
-                 int dtype, int32_t *idx, float *prob, float *logits_opt, void *ws, hipStream_t st, const char *who)
+                 int dtype, int top_k, int renormalize, int32_t *idx, float *prob, float *logits_opt, void *ws,
+                 hipStream_t st, const char *who)
 {
     if (route_uses_mfma(d, E, dtype)) {
         const void *wp = w_router;
@@ -187,7 +270,7 @@ int route_launch(const void *x, const void *w_router, int w_layout, const float 
         int grid = ceil_div(T, 32 * mbk);
 #define MOE_ROUTE_LAUNCH(NB_, MB_)                                                                            \
     hipLaunchKernelGGL((route_mfma_kernel<NB_, MB_>), dim3(grid), dim3(GEMM_THREADS), 0, st, (const bf16_t *)x, \
-                       (const bf16_t *)wp, b_router, T, d, idx, prob, logits_opt)
+                       (const bf16_t *)wp, b_router, T, d, top_k, renormalize, idx, prob, logits_opt)
         if (E == 128) {
             if (mbk == 1) MOE_ROUTE_LAUNCH(1, 1);
             else if (mbk == 2) MOE_ROUTE_LAUNCH(1, 2);
@@ -200,10 +283,10 @@ int route_launch(const void *x, const void *w_router, int w_layout, const float 
 #undef MOE_ROUTE_LAUNCH
     } else if (dtype == MOE_BF16) {
         hipLaunchKernelGGL(route_generic_kernel<true>, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, w_router, b_router, T,
-                           d, E, idx, prob, logits_opt);
+                           d, E, top_k, renormalize, idx, prob, logits_opt);
     } else {
         hipLaunchKernelGGL(route_generic_kernel<false>, dim3(ceil_div(T, 4)), dim3(256), 0, st, x, w_router, b_router,
-                           T, d, E, idx, prob, logits_opt);
+                           T, d, E, top_k, renormalize, idx, prob, logits_opt);
     }
     MOE_CHECK_LAUNCH(who);
     return MOE_OK;
@@ -225,24 +308,45 @@ extern "C" size_t moe_route_workspace_bytes(int T, int d, int E, int dtype)
     return route_ws_bytes(d, E, dtype);
 }
 
+static int route_checked(const char *who, const void *x, const void *w_router, int w_layout, const float *b_router,
+                         int T, int d, int E, int dtype, int top_k, int renormalize, int32_t *expert_idx,
+                         float *expert_prob, float *logits_opt, void *ws, size_t ws_bytes, void *stream)
+{
+    MOE_REQUIRE(w_layout == MOE_LAYOUT_PLAIN || w_layout == MOE_LAYOUT_PACKED, MOE_ERR_INVALID_ARG,
+                "%s: unknown weight layout %d", who, w_layout);
+    MOE_REQUIRE(T >= 0 && d > 0 && E > 0, MOE_ERR_INVALID_ARG, "%s: T=%d d=%d E=%d out of range", who, T, d, E);
+    MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_INVALID_ARG, "%s: unknown dtype %d", who, dtype);
+    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "%s: E=%d exceeds %d", who, E, MOE_MAX_EXPERTS);
+    MOE_REQUIRE(top_k >= 1 && top_k <= MOE_MAX_TOPK && top_k <= E, MOE_ERR_INVALID_ARG,
+                "%s: k=%d outside 1..min(%d, E=%d)", who, top_k, MOE_MAX_TOPK, E);
+    MOE_REQUIRE((long long)T * top_k <= 0x7fffffffLL, MOE_ERR_INVALID_ARG, "%s: T*k=%lld does not fit 31 bits", who,
+                (long long)T * top_k);
+    MOE_REQUIRE(renormalize == 0 || renormalize == 1, MOE_ERR_INVALID_ARG, "%s: renormalize must be 0 or 1", who);
+    MOE_REQUIRE(d % 8 == 0, MOE_ERR_INVALID_ARG, "%s: d=%d is not a multiple of 8", who, d);
+    MOE_REQUIRE(w_layout == MOE_LAYOUT_PLAIN || route_uses_mfma(d, E, dtype), MOE_ERR_UNSUPPORTED,
+                "%s: a packed router matrix needs bf16, E = 128 or 256 and d a multiple of %d", who, RT_BK);
+    if (T == 0) return MOE_OK;
+    MOE_REQUIRE(x && w_router && expert_idx && expert_prob, MOE_ERR_INVALID_ARG, "%s: null pointer", who);
+    MOE_REQUIRE(aligned16(x) && aligned16(w_router), MOE_ERR_INVALID_ARG, "%s: tensor misaligned", who);
+    size_t need = route_ws_bytes(d, E, dtype);
+    MOE_REQUIRE(ws && aligned16(ws) && ws_bytes >= need, MOE_ERR_WORKSPACE,
+                "%s: workspace of %zu bytes needed, %zu given", who, need, ws_bytes);
+    return route_launch(x, w_router, w_layout, b_router, T, d, E, dtype, top_k, renormalize, expert_idx, expert_prob,
+                        logits_opt, ws, (hipStream_t)stream, who);
+}
+
 extern "C" int moe_route(const void *x, const void *w_router, int w_layout, const float *b_router, int T, int d,
                          int E, int dtype, int32_t *expert_idx, float *expert_prob, float *logits_opt, void *ws,
                          size_t ws_bytes, void *stream)
 {
-    MOE_REQUIRE(w_layout == MOE_LAYOUT_PLAIN || w_layout == MOE_LAYOUT_PACKED, MOE_ERR_INVALID_ARG,
-                "moe_route: unknown weight layout %d", w_layout);
-    MOE_REQUIRE(T >= 0 && d > 0 && E > 0, MOE_ERR_INVALID_ARG, "moe_route: T=%d d=%d E=%d out of range", T, d, E);
-    MOE_REQUIRE(dtype == MOE_F32 || dtype == MOE_BF16, MOE_ERR_INVALID_ARG, "moe_route: unknown dtype %d", dtype);
-    MOE_REQUIRE(E <= MOE_MAX_EXPERTS, MOE_ERR_UNSUPPORTED, "moe_route: E=%d exceeds %d", E, MOE_MAX_EXPERTS);
-    MOE_REQUIRE(d % 8 == 0, MOE_ERR_INVALID_ARG, "moe_route: d=%d is not a multiple of 8", d);
-    MOE_REQUIRE(w_layout == MOE_LAYOUT_PLAIN || route_uses_mfma(d, E, dtype), MOE_ERR_UNSUPPORTED,
-                "moe_route: a packed router matrix needs bf16, E = 128 or 256 and d a multiple of %d", RT_BK);
-    if (T == 0) return MOE_OK;
-    MOE_REQUIRE(x && w_router && expert_idx && expert_prob, MOE_ERR_INVALID_ARG, "moe_route: null pointer");
-    MOE_REQUIRE(aligned16(x) && aligned16(w_router), MOE_ERR_INVALID_ARG, "moe_route: tensor misaligned");
-    size_t need = route_ws_bytes(d, E, dtype);
-    MOE_REQUIRE(ws && aligned16(ws) && ws_bytes >= need, MOE_ERR_WORKSPACE,
-                "moe_route: workspace of %zu bytes needed, %zu given", need, ws_bytes);
-    return route_launch(x, w_router, w_layout, b_router, T, d, E, dtype, expert_idx, expert_prob, logits_opt, ws,
-                        (hipStream_t)stream, "moe_route");
+    return route_checked("moe_route", x, w_router, w_layout, b_router, T, d, E, dtype, 1, 0, expert_idx, expert_prob,
+                         logits_opt, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_route_topk(const void *x, const void *w_router, int w_layout, const float *b_router, int T,
+                              int d, int E, int dtype, int k, int renormalize, int32_t *expert_idx,
+                              float *expert_weight, float *logits_opt, void *ws, size_t ws_bytes, void *stream)
+{
+    return route_checked("moe_route_topk", x, w_router, w_layout, b_router, T, d, E, dtype, k, renormalize, expert_idx,
+                         expert_weight, logits_opt, ws, ws_bytes, stream);
 }

@@ -218,6 +218,6 @@ extern "C" int sru_predict(const void *emb, const sru_weights *w, int B, int L, 
         if (rc != MOE_OK) return rc;
         cur = zbuf;
     }
-    return route_launch(cur, w->w_head, head_layout, w->b_head, T, n_h, w->n_out, MOE_BF16, pred_idx, (float *)(base + lay.prob),
+    return route_launch(cur, w->w_head, head_layout, w->b_head, T, n_h, w->n_out, MOE_BF16, 1, 0, pred_idx, (float *)(base + lay.prob),
                         logits_opt, base + lay.rws, st, "sru_predict/head");
 }

@@ -82,6 +82,22 @@ def test_invalid_arguments_are_rejected_on_the_host():
     # moe_combine
     assert L.moe_combine(p, p, p, p, 4, 64, 0, 2, p, None) == INV                     # residual flag
     assert L.moe_combine(p, q, p, p, 4, 64, 0, 0, q, None) == INV                     # out aliases x
+    # top-k entries
+    assert L.moe_route_topk(p, p, 0, None, 4, 64, 8, 0, 0, 0, p, p, None, p, 4096, None) == INV    # k = 0
+    assert L.moe_route_topk(p, p, 0, None, 4, 64, 8, 0, 9, 0, p, p, None, p, 4096, None) == INV    # k > MOE_MAX_TOPK
+    assert L.moe_route_topk(p, p, 0, None, 4, 64, 2, 0, 3, 0, p, p, None, p, 4096, None) == INV    # k > E
+    assert L.moe_route_topk(p, p, 0, None, 4, 64, 8, 0, 3, 2, p, p, None, p, 4096, None) == INV    # renormalize flag
+    assert L.moe_route_topk(p, p, 0, None, 4, 768, 128, 1, 3, 0, p, p, None, p, 16, None) == WS
+    assert L.moe_dispatch_topk(p, p, None, 4, 0, 64, 8, 1, 8, 0, p, p, p, p, p, p, p, p, p, 4096, None) == INV
+    assert L.moe_dispatch_topk(p, p, None, 1 << 30, 3, 64, 8, 1, 8, 0, p, p, p, p, p, p, p, p, p, 4096, None) == INV
+    assert L.moe_dispatch_topk(p, p, None, 4, 3, 64, 8, 1, 8, 0, p, p, p, p, p, p, None, p, p, 4096, None) == INV
+    assert L.moe_dispatch_topk(p, p, None, 4, 3, 64, 8, 1, 8, 0, p, p, p, p, p, p, p, p, None, 0, None) == WS
+    assert L.moe_expert_ffn_rows(p, 4, None, p, p, 0, p, p, p, 12, 8, 8, 64, 256, 0, 0, p, p, 1 << 30, None) == INV
+    assert L.moe_expert_ffn_rows(p, 0, p, p, p, 0, p, p, p, 12, 8, 8, 64, 256, 0, 0, p, p, 1 << 30, None) == INV
+    assert L.moe_expert_ffn_rows(p, 4, p, p, p, 0, p, p, p, 12, 8, 8, 64, 256, 0, 0, p, p, 16, None) == WS
+    assert L.moe_combine_topk(p, p, p, p, 4, 9, 64, 0, 0, p, None) == INV              # k
+    assert L.moe_combine_topk(p, q, p, p, 4, 3, 64, 0, 0, q, None) == INV              # out aliases x
+    assert L.moe_combine_topk(p, p, p, p, 4, 3, 6, 0, 0, p, None) == INV               # row bytes
     # sru_predict
     w = moe.binding.SruWeightsC(2, 768, 256, 128, 0, None, None, None, None, None, 0)
     assert L.sru_predict(p, C.byref(w), 8, 512, 0, p, None, p, 4096, None) == UNS   # fp32 not built
