@@ -61,6 +61,11 @@ def _workload(name):
         c["sru"]["attention"] = True
         return c, c["C"], ("10-layer SRU predictor with sparsemax attention (B=8 L=512 768->256, head 128) + "
                            "Switch-base-128 layer T=4096 d=768 F=3072 E=128 CF=1.25 R=16")
+    if name == "cfg2k3":
+        # top-3 routing on the workload-2 layer: 3 x 4096 assignments, slot capacity scaled by k
+        c = synth.config_inputs(2)
+        c["top_k"] = 3
+        return c, 3 * c["C"], "Switch-base-128 layer, top-3 routing: T=4096 d=768 F=3072 E=128 CF=1.25 R=16 Zipf(1.0)"
     if name == "cfg4":
         c = synth.config_inputs(4)
         return c, c["C"], "Switch-base-256 layer T=16384 d=768 F=3072 E=256 CF=1.0 R=32 Zipf(1.1)"
@@ -89,10 +94,18 @@ def _cpu_baseline(c, C, R, budget_s=20.0):
     whole batch, the expert FFN on a sample of kept rows sized to ~budget_s, scaled to K."""
     import oracle
     T, E = c["T"], c["E"]
+    k = c.get("top_k", 1)
     t0 = time.perf_counter()
-    rt = oracle.route(c["x"], c["w_router"], c["b_router"])
-    pl = oracle.plan(rt["idx"], E, R, C)
-    dp = oracle.dispatch(c["x"], rt["idx"], pl["replicas"], E, C, E + R)
+    if k == 1:
+        rt = oracle.route(c["x"], c["w_router"], c["b_router"])
+        pl = oracle.plan(rt["idx"], E, R, C)
+        dp = oracle.dispatch(c["x"], rt["idx"], pl["replicas"], E, C, E + R)
+    else:
+        from oracle import topk
+        rt = oracle.route_topk(c["x"], c["w_router"], c["b_router"], k)
+        ids = rt["idx"].reshape(-1)
+        pl = oracle.plan(ids, E, R, C)
+        dp = oracle.dispatch(topk.assignment_rows(c["x"], k), ids, pl["replicas"], E, C, E + R)
     t_front = time.perf_counter() - t0
     K = int(dp["expert_offset"][E])
     rng = np.random.default_rng(0)
@@ -106,7 +119,10 @@ def _cpu_baseline(c, C, R, budget_s=20.0):
     y = oracle.ffn(dp["x_perm"], c["w1"], c["w2"], dp["slot_offset"], pl["slot_expert"], pl["n_slots"], rows=rows)
     t_ffn = (time.perf_counter() - t0) * (K / n)
     t0 = time.perf_counter()
-    oracle.combine(y, c["x"], dp["inv"], rt["prob"], 0)
+    if k == 1:
+        oracle.combine(y, c["x"], dp["inv"], rt["prob"], 0)
+    else:
+        oracle.combine_topk(y, c["x"], dp["inv"].reshape(k, T), rt["weight"], 0)
     t_back = time.perf_counter() - t0
     total = t_front + t_ffn + t_back
     return dict(value=T / total, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
@@ -147,8 +163,13 @@ def main():
     w2 = moe.moe_pack_weights(_to_dev(c["w2"]))
     torch.cuda.synchronize()
 
-    layer = moe.MoeLayer(T, d, F, E, R, C, dt)
-    layer0 = moe.MoeLayer(T, d, F, E, 0, C, dt)          # budget 0: the plain Switch layer
+    top_k = c.get("top_k", 1)
+    if top_k == 1:
+        layer = moe.MoeLayer(T, d, F, E, R, C, dt)
+        layer0 = moe.MoeLayer(T, d, F, E, 0, C, dt)          # budget 0: the plain Switch layer
+    else:
+        layer = moe.MoeLayerTopK(T, d, F, E, top_k, R, C, dt)
+        layer0 = moe.MoeLayerTopK(T, d, F, E, top_k, 0, C, dt)
     sru = None
     if "sru" in c:
         s_ = c["sru"]
@@ -173,8 +194,11 @@ def main():
         if it["timed"]:
             moe.set_ffn_timing_events(*evs[it["i"]])
             it["i"] += 1
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED,
-                      plan_ids=plan_ids)
+        if plan_ids is None:
+            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED)
+        else:
+            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED,
+                          plan_ids=plan_ids)
 
     def step_off_same_plan():
         layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=moe.LAYOUT_PACKED)
@@ -257,7 +281,7 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_on, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": desc, "name": a.workload, "T": T, "d_model": d, "d_ff": F, "experts": E,
-                   "slot_capacity": C, "replica_budget": R, "kept_tokens": K, "active_experts": active,
+                   "top_k": top_k, "slot_capacity": C, "replica_budget": R, "kept_tokens": K, "active_experts": active,
                    "slots": n_slots, "replication": "on (slot schedule)"},
         "roofline": roofline,
         "cpu_baseline": cpu,
