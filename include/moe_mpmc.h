@@ -198,6 +198,21 @@ int moe_dispatch(const void *x, const int32_t *expert_idx, const int32_t *replic
                  int32_t *inv, void *x_perm, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
+ * moe_plan_dispatch -- replica_plan (Algorithm 1 with the budget cap) on plan_idx[n_plan], then the
+ * index tables of moe_dispatch (moe_dispatch_topk for k > 1) for expert_idx[k*T] under that plan, as
+ * one call: the same tables, bit for bit, as the two calls with max_slots = E + budget and no row
+ * copy.  Small batches (n_plan and k*T at most 8192, E at most 256) run in a single kernel and need no
+ * workspace; larger ones run the separate kernels.  row_token may be NULL when k = 1.
+ */
+size_t moe_plan_dispatch_workspace_bytes(int n_plan, int T, int k, int E);
+int moe_plan_dispatch(const int32_t *plan_idx, int n_plan, const int32_t *expert_idx, int T, int k,
+                      int E, int budget, int slot_capacity, int policy, int32_t *plan_counts,
+                      int32_t *replicas, int32_t *slot_base, int32_t *slot_expert, int32_t *n_slots,
+                      int32_t *counts, int32_t *kept, int32_t *expert_offset, int32_t *slot_offset,
+                      int32_t *perm, int32_t *inv, int32_t *row_token, void *ws, size_t ws_bytes,
+                      void *stream);
+
+/* ---------------------------------------------------------------------------------------
  * moe_pack_weights -- one-time re-layout of static expert weights for the bf16 matrix-core
  * kernels (inference weights do not change between batches).  Input w [E, K, N] row-major
  * bf16, K a multiple of 8, N a multiple of 32.  Output, in 16-byte pieces of 8 consecutive k:

@@ -28,6 +28,7 @@ EXPORTS = (
     "moe_expert_ffn_workspace_bytes", "moe_expert_ffn", "moe_expert_ffn_set_timing_events",
     "moe_combine",
     "moe_route_topk", "moe_dispatch_topk", "moe_expert_ffn_rows", "moe_combine_topk",
+    "moe_plan_dispatch_workspace_bytes", "moe_plan_dispatch",
 )
 
 
@@ -78,6 +79,8 @@ def lib():
         _lib.moe_dispatch_topk.argtypes = [P, P, P, I, I, I, I, I, I, I, P, P, P, P, P, P, P, P, P, S, P]
         _lib.moe_expert_ffn_rows.argtypes = [P, I, P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P]
         _lib.moe_combine_topk.argtypes = [P, P, P, P, I, I, I, I, I, P, P]
+        _lib.moe_plan_dispatch_workspace_bytes.argtypes = [I, I, I, I]
+        _lib.moe_plan_dispatch.argtypes = [P, I, P, I, I, I, I, I, I] + [P] * 12 + [P, S, P]
     return _lib
 
 
@@ -250,6 +253,36 @@ def moe_combine(y_perm, x, inv, expert_prob, residual=0, out=None):
     return o
 
 
+def moe_plan_dispatch(plan_idx, expert_idx, E, budget, slot_capacity, policy=0, plan_out=None, disp_out=None,
+                      ws=None):
+    """replica_plan on plan_idx, then moe_dispatch's index tables for expert_idx ([T] or [k,T]) under
+    that plan, in one call.  -> (plan dict, dispatch dict) with the keys of the separate calls
+    (dispatch: no x_perm; row_token when expert_idx is [k,T])."""
+    dev = expert_idx.device
+    k = expert_idx.shape[0] if expert_idx.dim() == 2 else 1
+    T = expert_idx.shape[-1]
+    A = k * T
+    max_slots = E + budget
+    po = plan_out if plan_out is not None else dict(plan_counts=_i32(E, dev), replicas=_i32(E, dev),
+                                                    slot_base=_i32(E + 1, dev), slot_expert=_i32(E + budget, dev),
+                                                    n_slots=_i32(1, dev))
+    do = disp_out if disp_out is not None else dict(
+        counts=_i32(E, dev), kept=_i32(E, dev), expert_offset=_i32(E + 1, dev), slot_offset=_i32(max_slots + 1, dev),
+        perm=_i32(A, dev), inv=_i32(A, dev).view(expert_idx.shape),
+        row_token=_i32(A, dev) if expert_idx.dim() == 2 else None, x_perm=None)
+    n_plan = plan_idx.numel()
+    if ws is None:
+        need = lib().moe_plan_dispatch_workspace_bytes(n_plan, T, k, E)
+        ws = _ws(need, dev) if need else None
+    _check(lib().moe_plan_dispatch(_ptr(plan_idx), n_plan, _ptr(expert_idx), T, k, E, budget, slot_capacity, policy,
+                                   _ptr(po["plan_counts"]), _ptr(po["replicas"]), _ptr(po["slot_base"]),
+                                   _ptr(po["slot_expert"]), _ptr(po["n_slots"]), _ptr(do["counts"]), _ptr(do["kept"]),
+                                   _ptr(do["expert_offset"]), _ptr(do["slot_offset"]), _ptr(do["perm"]),
+                                   _ptr(do["inv"]), _ptr(do.get("row_token")), _ptr(ws),
+                                   ws.numel() if ws is not None else 0, _stream()))
+    return po, do
+
+
 # --------------------------------------------------------------------------- top-k routing
 def moe_route_topk(x, w_router, b_router, k, renormalize=False, want_logits=False, out=None, ws=None,
                    w_layout=LAYOUT_PLAIN):
@@ -342,6 +375,7 @@ class MoeLayerTopK:
                              slot_offset=_i32(self.max_slots + 1, dev), perm=_i32(A, dev),
                              inv=_i32(A, dev).view(k, T), row_token=_i32(A, dev), x_perm=None)
         self.disp_ws = _ws(L.moe_dispatch_workspace_bytes(A, E), dev)
+        self.front_ws = _ws(L.moe_plan_dispatch_workspace_bytes(A, T, k, E), dev)
         self.y_perm = torch.zeros(A, d, dtype=dtype, device=dev)
         self.ffn_ws = _ws(L.moe_expert_ffn_workspace_bytes(A, self.max_slots, d, F, dt), dev)
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
@@ -350,10 +384,8 @@ class MoeLayerTopK:
                 out=None, router_layout=LAYOUT_PLAIN):
         idx, wgt, _ = moe_route_topk(x, w_router, b_router, self.k, self.renormalize, out=self.route_out,
                                      ws=self.route_ws, w_layout=router_layout)
-        pl = replica_plan(idx.view(-1) if plan_ids is None else plan_ids, self.E, self.R, self.C, self.policy,
-                          out=self.plan_out, ws=self.plan_ws)
-        dp = moe_dispatch_topk(None, idx, pl["replicas"], self.E, self.C, self.max_slots, out=self.disp_out,
-                               ws=self.disp_ws, shape=(self.T, self.d), dtype=x.dtype)
+        pl, dp = moe_plan_dispatch(idx.view(-1) if plan_ids is None else plan_ids, idx, self.E, self.R, self.C,
+                                   self.policy, plan_out=self.plan_out, disp_out=self.disp_out, ws=self.front_ws)
         y = moe_expert_ffn_rows(x, dp["row_token"], self.k * self.T, w1, w2, dp["slot_offset"], pl["slot_expert"],
                                 pl["n_slots"], self.E, self.F, max_slots=self.max_slots, schedule=schedule,
                                 out=self.y_perm, ws=self.ffn_ws)
@@ -381,6 +413,7 @@ class MoeLayer:
                              slot_offset=_i32(self.max_slots + 1, dev), perm=_i32(T, dev), inv=_i32(T, dev),
                              x_perm=torch.zeros(T, d, dtype=dtype, device=dev))
         self.disp_ws = _ws(L.moe_dispatch_workspace_bytes(T, E), dev)
+        self.front_ws = _ws(L.moe_plan_dispatch_workspace_bytes(T, T, 1, E), dev)
         self.y_perm = torch.zeros(T, d, dtype=dtype, device=dev)
         self.ffn_ws = _ws(L.moe_expert_ffn_workspace_bytes(T, self.max_slots, d, F, dt), dev)
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
@@ -394,10 +427,14 @@ class MoeLayer:
         R = self.R if budget is None else budget
         if R != self.R:
             raise ValueError("budget is fixed by the preallocated slot tables")
-        pl = plan if plan is not None else replica_plan(idx if plan_ids is None else plan_ids, self.E, R, self.C,
-                                                        self.policy, out=self.plan_out, ws=self.plan_ws)
-        dp = moe_dispatch(None if fuse_gather else x, idx, pl["replicas"], self.E, self.C, self.max_slots,
-                          out=self.disp_out, ws=self.disp_ws, shape=(self.T, self.d), dtype=x.dtype)
+        if plan is None and fuse_gather:
+            pl, dp = moe_plan_dispatch(idx if plan_ids is None else plan_ids, idx, self.E, R, self.C, self.policy,
+                                       plan_out=self.plan_out, disp_out=self.disp_out, ws=self.front_ws)
+        else:
+            pl = plan if plan is not None else replica_plan(idx if plan_ids is None else plan_ids, self.E, R,
+                                                            self.C, self.policy, out=self.plan_out, ws=self.plan_ws)
+            dp = moe_dispatch(None if fuse_gather else x, idx, pl["replicas"], self.E, self.C, self.max_slots,
+                              out=self.disp_out, ws=self.disp_ws, shape=(self.T, self.d), dtype=x.dtype)
         y = moe_expert_ffn(x if fuse_gather else dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"],
                            pl["n_slots"], self.E, self.F, max_slots=self.max_slots, schedule=schedule,
                            out=self.y_perm, ws=self.ffn_ws, row_index=dp["perm"] if fuse_gather else None)

@@ -8,49 +8,9 @@
 // owns experts l, l+64, ..., sums and arg-max searches are wavefront reductions, so the
 // one-by-one hand-out of the slots left by the floors needs no barrier.  All threads finally
 // scan the replica counts into slot_base and write the slot -> expert table.
-#include "common.h"
+#include "plan_alloc.h"
 
 namespace moe {
-
-constexpr int PLAN_THREADS = 1024;
-constexpr int PLAN_BATCH = 8;  // ids fetched per thread before any of them is counted
-
-__device__ __forceinline__ long long wave_sum_ll(long long v)
-{
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-
-constexpr int PLAN_BLOCK_TOKENS = PLAN_THREADS * PLAN_BATCH;   // ids per workgroup of the partial pass
-
-// ballot-aggregated LDS histogram of ids [t_begin, t_end)
-__device__ __forceinline__ void plan_histogram(const int32_t *__restrict__ idx, int t_begin, int t_end, int E,
-                                               int nbits, int *hist)
-{
-    const int tid = threadIdx.x, lane = tid & 63;
-    for (int t0 = t_begin; t0 < t_end; t0 += PLAN_THREADS * PLAN_BATCH) {
-        int eb[PLAN_BATCH];
-#pragma unroll
-        for (int u = 0; u < PLAN_BATCH; ++u) {
-            int t = t0 + u * PLAN_THREADS + tid;
-            eb[u] = t < t_end ? idx[t] : -1;
-        }
-#pragma unroll
-        for (int u = 0; u < PLAN_BATCH; ++u) {
-            int e = eb[u];
-            bool valid = e >= 0 && e < E;
-            unsigned long long mask = __ballot(valid);
-            if (mask == 0) continue;
-            for (int b = 0; b < nbits; ++b) {
-                bool bit = (e >> b) & 1;
-                unsigned long long bal = __ballot(bit);
-                mask &= bit ? bal : ~bal;
-            }
-            if (valid && (mask & ((1ull << lane) - 1ull)) == 0) atomicAdd(&hist[e], __popcll(mask));
-        }
-    }
-}
 
 // large batches: one workgroup per PLAN_BLOCK_TOKENS ids writes its histogram to partial[b][E]
 __global__ __launch_bounds__(PLAN_THREADS) void replica_plan_partial_kernel(const int32_t *__restrict__ idx, int T,
@@ -93,98 +53,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void replica_plan_kernel(
     if (n_partial == 0) plan_histogram(idx, 0, T, E, nbits, hist);
     __syncthreads();
 
-    if (tid < WAVE) {
-        int n[PLAN_PER_LANE], r[PLAN_PER_LANE];
-        long long want[PLAN_PER_LANE];
-        long long dsum = 0;
-#pragma unroll
-        for (int i = 0; i < PLAN_PER_LANE; ++i) {
-            int e = lane + i * WAVE;
-            n[i] = e < E ? hist[e] : 0;
-            long long w = ((long long)n[i] + C - 1) / C - 1;
-            want[i] = (e < E && w > 0) ? w : 0;
-            r[i] = 1;
-            dsum += want[i];
-        }
-        const long long D = wave_sum_ll(dsum);
-        if (D <= (long long)R) {
-#pragma unroll
-            for (int i = 0; i < PLAN_PER_LANE; ++i) r[i] += (int)want[i];
-        } else {
-            long long left = R;
-            if (policy == 0) {
-                long long used = 0;
-#pragma unroll
-                for (int i = 0; i < PLAN_PER_LANE; ++i) {
-                    long long extra = (long long)R * want[i] / D;
-                    r[i] += (int)extra;
-                    used += extra;
-                }
-                left -= wave_sum_ll(used);
-            } else {
-                for (;;) {
-                    long long nw = 0;
-#pragma unroll
-                    for (int i = 0; i < PLAN_PER_LANE; ++i) nw += (long long)r[i] - 1 < want[i];
-                    nw = wave_sum_ll(nw);
-                    if (nw == 0) break;
-                    long long q = left / nw;
-                    if (q == 0) break;
-                    long long given = 0;
-#pragma unroll
-                    for (int i = 0; i < PLAN_PER_LANE; ++i) {
-                        long long unmet = want[i] - ((long long)r[i] - 1);
-                        if (unmet > 0) {
-                            long long g = q < unmet ? q : unmet;
-                            r[i] += (int)g;
-                            given += g;
-                        }
-                    }
-                    left -= wave_sum_ll(given);
-                }
-            }
-            // the slots still left go one at a time to the most loaded expert per slot
-            while (left > 0) {
-                int bn = 0, br = 1, be = -1;
-#pragma unroll
-                for (int i = 0; i < PLAN_PER_LANE; ++i) {
-                    bool open = (long long)r[i] - 1 < want[i];
-                    // ascending expert id within the lane: strict '>' keeps the lowest id
-                    if (open && (be < 0 || (long long)n[i] * br > (long long)bn * r[i])) {
-                        bn = n[i];
-                        br = r[i];
-                        be = lane + i * WAVE;
-                    }
-                }
-#pragma unroll
-                for (int o = 32; o >= 1; o >>= 1) {
-                    int on = __shfl_xor(bn, o, 64), orr = __shfl_xor(br, o, 64), oe = __shfl_xor(be, o, 64);
-                    if (oe >= 0) {
-                        long long lhs = (long long)on * br, rhs = (long long)bn * orr;
-                        if (be < 0 || lhs > rhs || (lhs == rhs && oe < be)) {
-                            bn = on;
-                            br = orr;
-                            be = oe;
-                        }
-                    }
-                }
-                if (be < 0) break;
-#pragma unroll
-                for (int i = 0; i < PLAN_PER_LANE; ++i)
-                    if (be == lane + i * WAVE) r[i] += 1;
-                left -= 1;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < PLAN_PER_LANE; ++i) {
-            int e = lane + i * WAVE;
-            if (e < E) {
-                rep[e] = r[i];
-                replicas[e] = r[i];
-                plan_counts[e] = n[i];
-            }
-        }
-    }
+    if (tid < WAVE) plan_allocate_wave<PLAN_PER_LANE>(hist, rep, E, R, C, policy, replicas, plan_counts);
     __syncthreads();
 
     // slot_base = exclusive scan of the replica counts (one expert per thread)

@@ -98,6 +98,17 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.moe_combine_topk(p, p, p, p, 4, 9, 64, 0, 0, p, None) == INV              # k
     assert L.moe_combine_topk(p, q, p, p, 4, 3, 64, 0, 0, q, None) == INV              # out aliases x
     assert L.moe_combine_topk(p, p, p, p, 4, 3, 6, 0, 0, p, None) == INV               # row bytes
+    # moe_plan_dispatch
+    pd = lambda *a: L.moe_plan_dispatch(*a)
+    tabs = [p] * 12
+    assert pd(p, 4, p, 4, 1, 8, -1, 1, 0, *tabs, None, 0, None) == INV               # budget
+    assert pd(p, 4, p, 4, 0, 8, 2, 1, 0, *tabs, None, 0, None) == INV                # k
+    assert pd(p, 4, p, 4, 1, 8, 2, 1, 5, *tabs, None, 0, None) == INV                # policy
+    assert pd(p, 4, p, 4, 3, 8, 2, 1, 0, *([p] * 11), None, None, 0, None) == INV    # k > 1 without row_token
+    assert pd(p, 4, p, 4, 1, 4096, 2, 1, 0, *tabs, None, 0, None) == UNS
+    assert pd(p, 100000, p, 100000, 1, 8, 2, 1, 0, *tabs, None, 0, None) == WS
+    assert L.moe_plan_dispatch_workspace_bytes(4096, 4096, 1, 128) == 0
+    assert L.moe_plan_dispatch_workspace_bytes(4096, 4096, 3, 128) > 0
     # sru_predict
     w = moe.binding.SruWeightsC(2, 768, 256, 128, 0, None, None, None, None, None, 0)
     assert L.sru_predict(p, C.byref(w), 8, 512, 0, p, None, p, 4096, None) == UNS   # fp32 not built
