@@ -4,8 +4,8 @@
 // ONE workgroup of 1024 threads: the separate calls are three dependent launches (plan, histogram,
 // permute) of a few microseconds each in front of the expert FFN, each a chain of two or three memory
 // round trips, and at a few thousand tokens that chain is a tenth of the layer.  Steps:
-//   A  histogram of the plan ids (ballot-aggregated LDS atomics) and, from the routed ids, per 64-token
-//      chunk and expert the number of tokens (ballots; a token keeps its rank inside the chunk)
+//   A  histogram of the plan ids and, from the routed ids, per 64-token chunk and expert the number of
+//      tokens (lanes with equal ids are matched through LDS; a token keeps its rank inside the chunk)
 //   B  wavefront 0: the integer allocation of the plan; the other wavefronts: per expert, prefix of the
 //      chunk counts (two levels: inside segments of 8 chunks, then over the segments) and the total.
 //      When the plan ids ARE the routed ids, they are read and matched once for both.
@@ -65,7 +65,7 @@ __device__ __forceinline__ void expert_scan2(int v0, int v1, int &ex0, int &ex1,
 template <int PLAN_PER_LANE, bool SAME>
 __global__ __launch_bounds__(PLAN_THREADS) void plan_dispatch_small_kernel(
     const int32_t *__restrict__ plan_idx, int n_plan, const int32_t *__restrict__ idx, int T, int n_tokens, int E,
-    int nbits, int R, int C, int policy, int max_slots, int32_t *__restrict__ plan_counts,
+    int R, int C, int policy, int max_slots, int32_t *__restrict__ plan_counts,
     int32_t *__restrict__ replicas, int32_t *__restrict__ slot_base, int32_t *__restrict__ slot_expert,
     int32_t *__restrict__ n_slots, int32_t *__restrict__ counts, int32_t *__restrict__ kept,
     int32_t *__restrict__ expert_offset, int32_t *__restrict__ slot_offset, int32_t *__restrict__ perm,
@@ -73,6 +73,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_dispatch_small_kernel(
 {
     __shared__ unsigned short chunk_cnt[FRONT_CHUNKS][FRONT_LD];   // count, then prefix inside its segment
     __shared__ int seg_tot[FRONT_MAX_EXPERTS][FRONT_SEGS + 1];     // per expert: segment totals, then their prefix
+    __shared__ unsigned long long match[PLAN_THREADS / WAVE][FRONT_MAX_EXPERTS];   // per wavefront and expert: lanes
     __shared__ int hist[MOE_MAX_EXPERTS];
     __shared__ int rep[MOE_MAX_EXPERTS];
     __shared__ int tot_e[FRONT_MAX_EXPERTS], eoff_e[FRONT_MAX_EXPERTS], cap_e[FRONT_MAX_EXPERTS];
@@ -93,35 +94,36 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_dispatch_small_kernel(
         hist[e] = 0;
         rep[e] = 0;
     }
+    for (int i = lane; i < E; i += WAVE) match[w][i] = 0ull;
     for (int i = tid; i < n_segs * FRONT_SEG * (FRONT_LD / 2); i += PLAN_THREADS)
         reinterpret_cast<unsigned int *>(&chunk_cnt[0][0])[i] = 0u;
     __syncthreads();
 
-    // ---- A: match lanes with equal ids by one ballot per id bit
+    // ---- A: lanes of a wavefront with equal ids find each other through a 64-bit lane mask per expert in
+    // LDS (one atomic OR, one read, one clear per 64 ids; a ballot per id bit costs ~100 vector
+    // instructions per 64 ids, and with 16 wavefronts on one CU this step is bound by instruction issue)
+    auto match_lanes = [&](int e, bool valid) {
+        unsigned long long *slot = &match[w][valid ? e : 0];
+        if (valid) atomicOr(slot, 1ull << lane);
+        const unsigned long long m = valid ? __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : 0ull;
+        if (valid && (m & ((1ull << lane) - 1ull)) == 0)
+            __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);   // for the next 64 ids
+        return m;
+    };
 #pragma unroll
     for (int rd = 0; rd < FRONT_ROUNDS; ++rd) {
         const int c = rd * 16 + w;
         if (!SAME && c * WAVE < n_plan) {           // uniform per wavefront
             const int e = plan_e[rd];
             const bool valid = e >= 0 && e < E;
-            unsigned long long mask = __ballot(valid);
-            for (int b = 0; b < nbits; ++b) {
-                const bool bit = (e >> b) & 1;
-                const unsigned long long bal = __ballot(bit);
-                mask &= bit ? bal : ~bal;
-            }
+            const unsigned long long mask = match_lanes(e, valid);
             if (valid && (mask & ((1ull << lane) - 1ull)) == 0) atomicAdd(&hist[e], __popcll(mask));
         }
         my_rank[rd] = 0;
         if (c < n_chunks) {
             const int e = my_e[rd];
             const bool valid = e >= 0 && e < E;
-            unsigned long long mask = __ballot(valid);
-            for (int b = 0; b < nbits; ++b) {
-                const bool bit = (e >> b) & 1;
-                const unsigned long long bal = __ballot(bit);
-                mask &= bit ? bal : ~bal;
-            }
+            const unsigned long long mask = match_lanes(e, valid);
             const int rank = __popcll(mask & ((1ull << lane) - 1ull));
             if (valid && rank == 0) {
                 chunk_cnt[c][e] = (unsigned short)__popcll(mask);
@@ -277,13 +279,11 @@ extern "C" int moe_plan_dispatch(const int32_t *plan_idx, int n_plan, const int3
                                  counts, kept, expert_offset, slot_offset, perm, inv, row_token, nullptr,
                                  (char *)ws + plan_ws, ws_bytes - plan_ws, stream);
     }
-    int nbits = 0;
-    while ((1 << nbits) < E) ++nbits;
     const bool same = plan_idx == expert_idx && n_plan == A;
     auto kern = E <= 128 ? (same ? plan_dispatch_small_kernel<2, true> : plan_dispatch_small_kernel<2, false>)
                          : (same ? plan_dispatch_small_kernel<4, true> : plan_dispatch_small_kernel<4, false>);
     hipLaunchKernelGGL(kern, dim3(1), dim3(PLAN_THREADS), 0, (hipStream_t)stream, plan_idx, n_plan, expert_idx, A,
-                       T > 0 ? T : 1, E, nbits, budget, slot_capacity, policy, max_slots, plan_counts, replicas,
+                       T > 0 ? T : 1, E, budget, slot_capacity, policy, max_slots, plan_counts, replicas,
                        slot_base, slot_expert, n_slots, counts, kept, expert_offset, slot_offset, perm, inv,
                        row_token);
     MOE_CHECK_LAUNCH("moe_plan_dispatch");
