@@ -138,7 +138,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_dispatch_small_kernel(
     // ---- B: wavefront 0 runs the allocation; the others the prefix of the chunk counts inside segments of
     // 8 chunks (one expert and segment per thread)
     if (tid < WAVE) {
-        plan_allocate_wave<PLAN_PER_LANE>(hist, rep, E, R, C, policy, replicas, plan_counts);
+        plan_allocate_wave<PLAN_PER_LANE>(hist, rep, SAME ? T : n_plan, E, R, C, policy, replicas, plan_counts);
     } else {
         for (int i = tid - WAVE; i < E * n_segs; i += PLAN_THREADS - WAVE) {
             const int e = i % E, g = i / E;

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void replica_plan_kernel(
     if (n_partial == 0) plan_histogram(idx, 0, T, E, nbits, hist);
     __syncthreads();
 
-    if (tid < WAVE) plan_allocate_wave<PLAN_PER_LANE>(hist, rep, E, R, C, policy, replicas, plan_counts);
+    if (tid < WAVE) plan_allocate_wave<PLAN_PER_LANE>(hist, rep, T, E, R, C, policy, replicas, plan_counts);
     __syncthreads();
 
     // slot_base = exclusive scan of the replica counts (one expert per thread)

@@ -98,11 +98,12 @@ __device__ __forceinline__ double row_exchange_f64(double v)
 
 // The allocation of Algorithm 1 with the budget cap, run by ONE wavefront entirely in registers (lane l
 // owns experts l, l+64, ...; sums and arg-max searches are wavefront reductions, so the one-by-one
-// hand-out of the slots left by the floors needs no barrier).  hist: counts per expert (LDS).
+// hand-out of the slots left by the floors needs no barrier).  hist: counts per expert (LDS), n_ids: their
+// sum at most.
 // Writes rep[e] (LDS) and the replicas / plan_counts tables.
 template <int PLAN_PER_LANE>
-__device__ __forceinline__ void plan_allocate_wave(const int *hist, int *rep, int E, int R, int C, int policy,
-                                                   int32_t *__restrict__ replicas,
+__device__ __forceinline__ void plan_allocate_wave(const int *hist, int *rep, int n_ids, int E, int R, int C,
+                                                   int policy, int32_t *__restrict__ replicas,
                                                    int32_t *__restrict__ plan_counts)
 {
     const int lane = threadIdx.x & 63;
@@ -161,6 +162,47 @@ __device__ __forceinline__ void plan_allocate_wave(const int *hist, int *rep, in
         // the slots still left go one at a time to the most loaded expert per slot.  A dependent chain of
         // up to R steps on one wavefront: rows of 16 lanes are folded by lane exchanges, the four rows as
         // scalars (shuffles routed through LDS and cross products made each step ~2000 cycles)
+        if (n_ids < (1 << 24)) {
+            // Counts below 2^24: load per slot and expert id in ONE 64-bit integer, so a fold step is an
+            // unsigned maximum.  q = floor(RN(n 2^28 / r)) is monotone in n / r, equal for equal fractions,
+            // and different fractions differ by 2^28 / (r r') >= 4 (r <= 2^13), so the order of the q is the
+            // exact order of the fractions; the low 10 bits hold 1023 - id (lower id wins among equals);
+            // 0 = no candidate (an open expert has n > C >= 1, so its q is positive).
+            auto slot_key = [&](int i) -> unsigned long long {
+                const bool open = (long long)r[i] - 1 < want[i];
+                const unsigned long long q = (unsigned long long)((double)n[i] * 268435456.0 / (double)r[i]);
+                return open ? (q << 10) | (unsigned long long)(1023 - (lane + i * WAVE)) : 0ull;
+            };
+            auto umax = [](unsigned long long a, unsigned long long b) { return a > b ? a : b; };
+            unsigned long long key[PLAN_PER_LANE];
+#pragma unroll
+            for (int i = 0; i < PLAN_PER_LANE; ++i) key[i] = slot_key(i);
+            while (left > 0) {
+                unsigned long long bk = 0ull;
+#pragma unroll
+                for (int i = 0; i < PLAN_PER_LANE; ++i) bk = umax(bk, key[i]);
+                bk = umax(bk, (unsigned long long)row_exchange_ll<0>((long long)bk));
+                bk = umax(bk, (unsigned long long)row_exchange_ll<1>((long long)bk));
+                bk = umax(bk, (unsigned long long)row_exchange_ll<2>((long long)bk));
+                bk = umax(bk, (unsigned long long)row_exchange_ll<3>((long long)bk));
+                unsigned long long sk = 0ull;
+#pragma unroll
+                for (int row = 0; row < 4; ++row) {
+                    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)bk, 16 * row);
+                    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(bk >> 32), 16 * row);
+                    sk = umax(sk, ((unsigned long long)hi << 32) | lo);
+                }
+                if (sk == 0ull) break;
+                const int be = 1023 - (int)(sk & 1023ull);
+#pragma unroll
+                for (int i = 0; i < PLAN_PER_LANE; ++i)
+                    if (be == lane + i * WAVE) {
+                        r[i] += 1;
+                        key[i] = slot_key(i);
+                    }
+                left -= 1;
+            }
+        } else {
         double key[PLAN_PER_LANE];
 #pragma unroll
         for (int i = 0; i < PLAN_PER_LANE; ++i) key[i] = load_per_slot(n[i], r[i]);
@@ -197,6 +239,7 @@ __device__ __forceinline__ void plan_allocate_wave(const int *hist, int *rep, in
                     key[i] = load_per_slot(n[i], r[i]);
                 }
             left -= 1;
+        }
         }
     }
 #pragma unroll

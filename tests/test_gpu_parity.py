@@ -55,6 +55,48 @@ def test_plan_bit_exact_random(policy):
         assert int(got["n_slots"].item()) == ref["n_slots"]
 
 
+@pytest.mark.parametrize("policy", [0, 1])
+def test_plan_hand_out_ties_and_long_tail(policy):
+    """Cases made for the slot-by-slot hand-out after the floors: many experts with equal load per slot
+    (the lower id must win every tie), a budget far below the wants, and wants met one slot at a time."""
+    cases = []
+    E, C = 128, 10
+    counts = np.full(E, 25)                     # all equal: 2 extra slots wanted each, 37 to hand out
+    cases.append((counts, 37, C))
+    counts = np.array([100 - (i % 7) for i in range(300)])   # blocks of equal loads, R below the wants
+    cases.append((counts, 64, 9))
+    counts = np.array([1000, 999, 501, 500, 250, 3, 2, 1, 0, 0])
+    cases.append((counts, 13, 17))
+    counts = np.array([60, 40, 40, 20, 20, 20] * 20)          # equal fractions n/r across different n and r
+    cases.append((counts, 50, 10))
+    rng = np.random.default_rng(77)
+    for counts, R, C in cases:
+        E = len(counts)
+        ids = np.repeat(np.arange(E), counts).astype(np.int32)
+        rng.shuffle(ids)
+        ref = oracle.plan(ids, E, R, C, policy)
+        got = moe.replica_plan(to_dev(ids), E, R, C, policy)
+        assert (to_host(got["replicas"]) == ref["replicas"]).all(), (E, R, C)
+        assert (to_host(got["slot_expert"]) == ref["slot_expert"]).all()
+        assert ref["replicas"].sum() == E + R                  # the budget binds in every case
+        if len(ids) <= 8192 and E <= 256:
+            gp, _ = moe.moe_plan_dispatch(to_dev(ids), to_dev(ids[::-1].copy()), E, R, C, policy)
+            assert (to_host(gp["replicas"]) == ref["replicas"]).all()
+
+
+@pytest.mark.timeout(300)
+def test_plan_above_2_pow_24_ids():
+    """More than 2^24 ids: counts beyond the range of the packed hand-out keys (the binary64 keys run)."""
+    T, E, R, C = (1 << 24) + 12345, 64, 20, 150000
+    rng = np.random.default_rng(5)
+    ids = rng.choice(E, size=T, p=synth.zipf_weights(E, 0.9)).astype(np.int32)
+    ref = oracle.plan(ids, E, R, C)
+    got = moe.replica_plan(to_dev(ids), E, R, C)
+    assert (to_host(got["plan_counts"]) == ref["counts"]).all()
+    assert (to_host(got["replicas"]) == ref["replicas"]).all()
+    assert ref["counts"].max() >= (1 << 21) and ref["replicas"].sum() == E + R
+
+
 def test_plan_paper_scenario_on_gpu():
     ids = np.array([5] * 32 + [9] * 32, np.int32)
     np.random.default_rng(0).shuffle(ids)
