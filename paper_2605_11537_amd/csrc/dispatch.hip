@@ -10,7 +10,8 @@
 //            (LDS table) + rank inside the chunk (wavefront ballots, one per id bit);
 //            writes inv / perm
 //   gather   whole-chip copy of the kept rows, x_perm[pos] = x[perm[pos]], 16-byte accesses
-#include "common.h"
+#include "plan_alloc.h"
+#include "route.h"
 
 namespace moe {
 
@@ -67,11 +68,23 @@ __device__ __forceinline__ void block_scan4_256(const int (&v)[4], int (&excl)[4
 // histograms, the per-expert totals, its own prefix over earlier blocks, the kept counts and
 // the expert offsets (a few KB of reads; cheaper than a separate single-workgroup launch in
 // the dependency chain); workgroup 0 also writes those tables and the slot offsets out.
+//
+// PPL > 0: the replica plan is made here as well (PPL = experts per lane of the allocating wavefront), by
+// every workgroup for itself from the same counts -- the plan's own ids' histograms in plan_partial, or, when
+// that is NULL, the routed ids' totals just rebuilt (a plan made from the routed ids themselves) -- so the
+// plan kernels and their place in the dependency chain go away; workgroup 0 writes the plan's tables.
+struct PlanArgs {
+    const int32_t *plan_partial;
+    int n_partial, n_plan_ids, R, policy;
+    int32_t *plan_counts, *replicas, *slot_base, *slot_expert, *n_slots;
+};
+
+template <int PPL>
 __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
     const int32_t *__restrict__ idx, const int32_t *__restrict__ replicas, int T, int E, int nbits, int C, int nb,
     int max_slots, const int32_t *__restrict__ block_hist, int32_t *__restrict__ counts, int32_t *__restrict__ kept,
     int32_t *__restrict__ expert_offset, int32_t *__restrict__ slot_offset, int32_t *__restrict__ perm,
-    int32_t *__restrict__ inv, int n_tokens, int32_t *__restrict__ row_token)
+    int32_t *__restrict__ inv, int n_tokens, int32_t *__restrict__ row_token, PlanArgs pa)
 {
     __shared__ unsigned short chunk_cnt[DSP_CHUNKS][MOE_MAX_EXPERTS];
     __shared__ int before_e[MOE_MAX_EXPERTS];   // tokens of e in earlier blocks
@@ -79,6 +92,8 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
     __shared__ int cap_e[MOE_MAX_EXPERTS];      // kept count of e
     __shared__ int wave_sums[4];
     __shared__ int total_k, total_p;
+    __shared__ int plan_hist[PPL > 0 ? MOE_MAX_EXPERTS : 1];
+    __shared__ int rep[PPL > 0 ? MOE_MAX_EXPERTS : 1];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int base = blockIdx.x * DSP_TOKENS;
     for (int i = tid; i < DSP_CHUNKS * E; i += DSP_THREADS) chunk_cnt[i / E][i % E] = 0;
@@ -92,12 +107,33 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
             bef += b < (int)blockIdx.x ? v : 0;
             tot += v;
         }
-        int r = replicas ? replicas[e] : 1;
-        if (r < 1) r = 1;
-        long long cap = (long long)r * C;
         before_e[e] = bef;
-        cap_e[e] = (long long)tot < cap ? tot : (int)cap;
         eoff_e[e] = tot;      // total count, replaced by the offset below
+        if (PPL > 0) {
+            int h = tot;
+            if (pa.plan_partial) {
+                h = 0;
+                for (int b = 0; b < pa.n_partial; ++b) h += pa.plan_partial[(size_t)b * E + e];
+            }
+            plan_hist[e] = h;
+        } else {
+            int r = replicas ? replicas[e] : 1;
+            if (r < 1) r = 1;
+            long long cap = (long long)r * C;
+            cap_e[e] = (long long)tot < cap ? tot : (int)cap;
+        }
+    }
+    if (PPL > 0) {
+        for (int e = E + tid; e < MOE_MAX_EXPERTS; e += DSP_THREADS) plan_hist[e] = 0;
+        __syncthreads();
+        if (tid < WAVE)
+            plan_allocate_wave<(PPL > 0 ? PPL : 1)>(plan_hist, rep, pa.n_plan_ids, E, pa.R, C, pa.policy, pa.replicas,
+                                                    pa.plan_counts, blockIdx.x == 0);
+        __syncthreads();
+        for (int e = tid; e < E; e += DSP_THREADS) {
+            const long long cap = (long long)rep[e] * C;
+            cap_e[e] = (long long)eoff_e[e] < cap ? eoff_e[e] : (int)cap;
+        }
     }
     __syncthreads();
     // Pass 2: thread t owns experts 4t..4t+3 for the scans over experts
@@ -107,7 +143,7 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
         int e = tid * 4 + i;
         n4[i] = e < E ? eoff_e[e] : 0;
         k4[i] = e < E ? cap_e[e] : 0;
-        int r = (e < E) ? (replicas ? replicas[e] : 1) : 0;
+        int r = (e < E) ? (PPL > 0 ? rep[e] : (replicas ? replicas[e] : 1)) : 0;
         if (e < E && r < 1) r = 1;
         r4[i] = r;
     }
@@ -135,11 +171,24 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
                         if (p <= max_slots) slot_offset[p] = off4[i] + k * q + (k < rem ? k : rem);
                     }
                 }
+                if (PPL > 0) {
+                    if (pa.slot_base) pa.slot_base[e] = sb4[i];
+                    if (pa.slot_expert)
+                        for (int k = 0; k < r4[i]; ++k) pa.slot_expert[sb4[i] + k] = e;
+                }
             }
         }
         if (tid == 0) expert_offset[E] = K;
         if (slot_offset)
             for (int p = P + tid; p <= max_slots; p += DSP_THREADS) slot_offset[p] = K;
+        if (PPL > 0) {
+            if (tid == 0) {
+                if (pa.slot_base) pa.slot_base[E] = P;
+                if (pa.n_slots) pa.n_slots[0] = P;
+            }
+            if (pa.slot_expert)
+                for (int p = P + tid; p < E + pa.R; p += DSP_THREADS) pa.slot_expert[p] = -1;
+        }
     }
     __syncthreads();
     if (T == 0) return;
@@ -231,6 +280,36 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_gather_kernel(const uint
         if (c + u * 32 < vec_per_row) dst[c + u * 32] = v[u];
 }
 
+size_t dispatch_block_hist_bytes(int T, int E)
+{
+    size_t nb = (size_t)ceil_div(T, DSP_TOKENS);
+    return align_up((nb > 0 ? nb : 1) * (size_t)E * sizeof(int32_t), 256);
+}
+
+int dispatch_planned_launch(const int32_t *expert_idx, int T, int n_tokens, int E, int slot_capacity, int budget,
+                            int policy, const int32_t *plan_partial, int n_partial, int n_plan_ids,
+                            int32_t *block_hist, int32_t *plan_counts, int32_t *replicas, int32_t *slot_base,
+                            int32_t *slot_expert, int32_t *n_slots, int32_t *counts, int32_t *kept,
+                            int32_t *expert_offset, int32_t *slot_offset, int32_t *perm, int32_t *inv,
+                            int32_t *row_token, hipStream_t st, const char *who)
+{
+    const int nb = ceil_div(T, DSP_TOKENS);
+    if (nb > 0) {
+        hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nb), dim3(DSP_THREADS), 0, st, expert_idx, T, E, block_hist);
+        MOE_CHECK_LAUNCH(who);
+    }
+    int nbits = 0;
+    while ((1 << nbits) < E) ++nbits;
+    PlanArgs pa{plan_partial, n_partial, n_plan_ids, budget, policy, plan_counts, replicas, slot_base, slot_expert,
+                n_slots};
+    auto kern = E <= 128 ? dispatch_permute_kernel<2> : E <= 256 ? dispatch_permute_kernel<4> : dispatch_permute_kernel<16>;
+    hipLaunchKernelGGL(kern, dim3(nb > 0 ? nb : 1), dim3(DSP_THREADS), 0, st, expert_idx, (const int32_t *)nullptr, T, E,
+                       nbits, slot_capacity, nb, E + budget, block_hist, counts, kept, expert_offset, slot_offset, perm,
+                       inv, n_tokens > 0 ? n_tokens : 1, row_token, pa);
+    MOE_CHECK_LAUNCH(who);
+    return MOE_OK;
+}
+
 }  // namespace moe
 
 using namespace moe;
@@ -275,9 +354,9 @@ static int dispatch_checked(const char *who, const void *x, const int32_t *exper
     {
         int nbits = 0;
         while ((1 << nbits) < E) ++nbits;
-        hipLaunchKernelGGL(dispatch_permute_kernel, dim3(nb > 0 ? nb : 1), dim3(DSP_THREADS), 0, st, expert_idx,
+        hipLaunchKernelGGL(dispatch_permute_kernel<0>, dim3(nb > 0 ? nb : 1), dim3(DSP_THREADS), 0, st, expert_idx,
                            replicas, T, E, nbits, slot_capacity, nb, max_slots, block_hist, counts, kept,
-                           expert_offset, slot_offset, perm, inv, n_tokens > 0 ? n_tokens : 1, row_token);
+                           expert_offset, slot_offset, perm, inv, n_tokens > 0 ? n_tokens : 1, row_token, PlanArgs{});
         MOE_CHECK_LAUNCH(who);
         if (x && nb > 0) {
             int vec_per_row = (int)((size_t)d * esz / 16);

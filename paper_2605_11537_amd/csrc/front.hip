@@ -12,8 +12,10 @@
 //   C  per expert: kept = min(total, replicas * C); scans over experts for the first row of every expert
 //      and the first slot; slot tables
 //   D  per token: row = first row of its expert + prefix of its chunk + rank in the chunk, if kept
-// Larger inputs go through the two separate calls.  Same tables, bit for bit, either way.
+// Larger inputs: block histograms of the ids, then the dispatch's permute kernel with the plan made inside it
+// (every workgroup for itself), two or three launches instead of four.  Same tables, bit for bit, either way.
 #include "plan_alloc.h"
+#include "route.h"
 
 namespace moe {
 
@@ -237,7 +239,8 @@ extern "C" size_t moe_plan_dispatch_workspace_bytes(int n_plan, int T, int k, in
 {
     if (n_plan < 0 || T < 0 || k < 1 || E <= 0 || (long long)T * k > 0x7fffffffLL) return 0;
     if (front_fused(n_plan, T * k, E)) return 0;
-    return align_up(replica_plan_workspace_bytes(n_plan, E), 256) + moe_dispatch_workspace_bytes(T * k, E);
+    return dispatch_block_hist_bytes(T * k, E) +
+           align_up((size_t)(ceil_div(n_plan, plan_partial_block()) + 1) * E * sizeof(int32_t), 256);
 }
 
 extern "C" int moe_plan_dispatch(const int32_t *plan_idx, int n_plan, const int32_t *expert_idx, int T, int k,
@@ -262,24 +265,30 @@ extern "C" int moe_plan_dispatch(const int32_t *plan_idx, int n_plan, const int3
                 MOE_ERR_INVALID_ARG, "moe_plan_dispatch: null pointer");
     MOE_REQUIRE(k == 1 || A == 0 || row_token, MOE_ERR_INVALID_ARG, "moe_plan_dispatch: null row_token with k > 1");
     const int max_slots = E + budget;
+    const bool same = plan_idx == expert_idx && n_plan == A;
     if (!front_fused(n_plan, A, E)) {
-        const size_t plan_ws = align_up(replica_plan_workspace_bytes(n_plan, E), 256);
-        const size_t need = plan_ws + moe_dispatch_workspace_bytes(A, E);
+        // block histograms of the routed ids (and of the plan ids, if they are others), then one kernel that
+        // makes the plan and the permutation
+        const size_t hist_bytes = dispatch_block_hist_bytes(A, E);
+        const size_t need = moe_plan_dispatch_workspace_bytes(n_plan, T, k, E);
         MOE_REQUIRE(ws && aligned16(ws) && ws_bytes >= need, MOE_ERR_WORKSPACE,
                     "moe_plan_dispatch: workspace of %zu bytes needed, %zu given", need, ws_bytes);
-        int rc = replica_plan(plan_idx, n_plan, E, budget, slot_capacity, policy, plan_counts, replicas, slot_base,
-                              slot_expert, n_slots, ws, plan_ws, stream);
-        if (rc != MOE_OK) return rc;
-        // row size: tables only, any valid value
-        if (k == 1 && !row_token)
-            return moe_dispatch(nullptr, expert_idx, replicas, T, 8, E, slot_capacity, max_slots, MOE_BF16, counts,
-                                kept, expert_offset, slot_offset, perm, inv, nullptr, (char *)ws + plan_ws,
-                                ws_bytes - plan_ws, stream);
-        return moe_dispatch_topk(nullptr, expert_idx, replicas, T, k, 8, E, slot_capacity, max_slots, MOE_BF16,
-                                 counts, kept, expert_offset, slot_offset, perm, inv, row_token, nullptr,
-                                 (char *)ws + plan_ws, ws_bytes - plan_ws, stream);
+        int32_t *block_hist = (int32_t *)ws;
+        int32_t *partial = nullptr;
+        int n_partial = 0;
+        if (!same) {
+            partial = (int32_t *)((char *)ws + hist_bytes);
+            n_partial = ceil_div(n_plan, plan_partial_block());
+            if (n_partial > 0) {
+                int rc = plan_partial_launch(plan_idx, n_plan, E, partial, (hipStream_t)stream, "moe_plan_dispatch");
+                if (rc != MOE_OK) return rc;
+            }
+        }
+        return dispatch_planned_launch(expert_idx, A, T, E, slot_capacity, budget, policy, partial, n_partial,
+                                       same ? A : n_plan, block_hist, plan_counts, replicas, slot_base, slot_expert,
+                                       n_slots, counts, kept, expert_offset, slot_offset, perm, inv, row_token,
+                                       (hipStream_t)stream, "moe_plan_dispatch");
     }
-    const bool same = plan_idx == expert_idx && n_plan == A;
     auto kern = E <= 128 ? (same ? plan_dispatch_small_kernel<2, true> : plan_dispatch_small_kernel<2, false>)
                          : (same ? plan_dispatch_small_kernel<4, true> : plan_dispatch_small_kernel<4, false>);
     hipLaunchKernelGGL(kern, dim3(1), dim3(PLAN_THREADS), 0, (hipStream_t)stream, plan_idx, n_plan, expert_idx, A,

@@ -9,6 +9,7 @@
 // one-by-one hand-out of the slots left by the floors needs no barrier.  All threads finally
 // scan the replica counts into slot_base and write the slot -> expert table.
 #include "plan_alloc.h"
+#include "route.h"
 
 namespace moe {
 
@@ -90,6 +91,18 @@ __global__ __launch_bounds__(PLAN_THREADS) void replica_plan_kernel(
     }
     if (slot_expert)
         for (int p = P + tid; p < E + R; p += PLAN_THREADS) slot_expert[p] = -1;
+}
+
+int plan_partial_block() { return PLAN_BLOCK_TOKENS; }
+
+int plan_partial_launch(const int32_t *idx, int T, int E, int32_t *partial, hipStream_t st, const char *who)
+{
+    int nbits = 0;
+    while ((1 << nbits) < E) ++nbits;
+    hipLaunchKernelGGL(replica_plan_partial_kernel, dim3(ceil_div(T, PLAN_BLOCK_TOKENS)), dim3(PLAN_THREADS), 0, st, idx,
+                       T, E, nbits, partial);
+    MOE_CHECK_LAUNCH(who);
+    return MOE_OK;
 }
 
 }  // namespace moe

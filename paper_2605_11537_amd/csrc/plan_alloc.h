@@ -100,11 +100,11 @@ __device__ __forceinline__ double row_exchange_f64(double v)
 // owns experts l, l+64, ...; sums and arg-max searches are wavefront reductions, so the one-by-one
 // hand-out of the slots left by the floors needs no barrier).  hist: counts per expert (LDS), n_ids: their
 // sum at most.
-// Writes rep[e] (LDS) and the replicas / plan_counts tables.
+// Writes rep[e] (LDS) and, with write_tables, the replicas / plan_counts tables.
 template <int PLAN_PER_LANE>
 __device__ __forceinline__ void plan_allocate_wave(const int *hist, int *rep, int n_ids, int E, int R, int C,
                                                    int policy, int32_t *__restrict__ replicas,
-                                                   int32_t *__restrict__ plan_counts)
+                                                   int32_t *__restrict__ plan_counts, bool write_tables = true)
 {
     const int lane = threadIdx.x & 63;
     int n[PLAN_PER_LANE], r[PLAN_PER_LANE];
@@ -247,8 +247,10 @@ __device__ __forceinline__ void plan_allocate_wave(const int *hist, int *rep, in
         int e = lane + i * WAVE;
         if (e < E) {
             rep[e] = r[i];
-            replicas[e] = r[i];
-            plan_counts[e] = n[i];
+            if (write_tables) {
+                replicas[e] = r[i];
+                plan_counts[e] = n[i];
+            }
         }
     }
 }
