@@ -1,4 +1,4 @@
-"""Pins for the oracle's sparsemax attention (survey row f3), independent of the oracle's own
+"""Pins for the oracle's sparsemax attention, independent of the oracle's own
 formula: closed forms, invariants, a bisection solve of the projection, and limiting cases of the
 attention in which the result is known without computing it."""
 import numpy as np
