@@ -137,6 +137,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing")
     ap.add_argument("--pmc-calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a reference dispatch of known size for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -236,6 +237,23 @@ def main():
                     ffn_mfma_tflops=round(2 * flops / ((g1 + g2) * 1e-3) / 1e12, 2),
                     ffn_mfma_frac_of_bf16_peak=round(2 * flops / ((g1 + g2) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4))
 
+    # the same step captured once into a HIP graph and replayed (the library allocates nothing, records no
+    # memset and never synchronises, so the whole chain of launches is capturable)
+    graph_ms = None
+    if not a.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step_on()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step_on()
+        for _ in range(a.warmup):
+            g.replay()
+        graph_ms = _time_steps(g.replay, a.steps)
+
     pipeline = None
     if sru is not None:
         # the paper's two threads as two streams: predictor + plan of batch i+1 under the layer of batch i
@@ -288,6 +306,7 @@ def main():
         "replication_modes_tokens_per_s": modes,
         "replication_modes_ms": extra_ms,
         "ms_per_step_with_kernel_events": round(ms_on_events, 5),
+        "ms_per_step_hip_graph_replay": None if graph_ms is None else round(graph_ms, 5),
         "kept_tokens_budget0": kept0,
     }
     if pipeline is not None:

@@ -94,3 +94,40 @@ def test_plan_dispatch_repeated_calls_reuse_buffers():
     assert (to_host(gp["slot_expert"]) == pl["slot_expert"]).all()
     for name in ("kept", "slot_offset", "perm", "inv"):
         assert (to_host(gd[name]) == dp[name]).all(), name
+
+
+def test_layer_forward_replays_from_a_hip_graph():
+    """The whole layer is a fixed sequence of launches on preallocated buffers (no allocation, no memset,
+    no synchronisation inside the library), so it can be captured once and replayed.  Every replay, with
+    new token values in the captured input buffer and eager work in between, equals the eager result."""
+    import paper_2605_11537_amd as moe
+    T, d, F, E, R, C = 2000, 128, 256, 16, 6, 150
+    c = synth.moe_layer_inputs(T, d, F, E, synth.BF16, 1.2, 555)
+    layer = moe.MoeLayer(T, d, F, E, R, C, torch.bfloat16)
+    eager = moe.MoeLayer(T, d, F, E, R, C, torch.bfloat16)
+    wr, b = to_dev(c["w_router"]), to_dev(c["b_router"])
+    w1, w2 = moe.moe_pack_weights(to_dev(c["w1"])), moe.moe_pack_weights(to_dev(c["w2"]))
+    x_static = to_dev(c["x"]).clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(2):
+            layer.forward(x_static, wr, b, w1, w2, residual=1)       # warm up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        out_static = layer.forward(x_static, wr, b, w1, w2, residual=1)
+    plans = set()
+    for i in range(4):
+        x_new = synth.normal_tensor((T, d), 1.0 + 0.5 * i, [556, i], synth.BF16)
+        x_static.copy_(to_dev(x_new))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out_static.clone()
+        want = eager.forward(to_dev(x_new), wr, b, w1, w2, residual=1)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"replay {i}"
+        assert torch.equal(layer.disp_out["inv"], eager.disp_out["inv"])
+        plans.add(tuple(to_host(layer.plan_out["replicas"]).tolist()))
+    assert len(plans) > 1                                            # the replays really planned anew
