@@ -53,8 +53,13 @@ __device__ __forceinline__ float tanhf_(float v)
 }
 
 // grid (n_h/16, B); block = 16 channels x 64 time chunks.  Phase 1: every thread composes its
-// chunk into (A, B) with c_out = A*c_in + B.  Phase 2: one thread per channel chains the 64
-// carries.  Phase 3: every thread re-runs its chunk from its true carry-in and writes h_t.
+// chunk into (A, B) with c_out = A*c_in + B.  Phase 2: one wavefront per channel composes the 64
+// chunk maps by a scan.  Phase 3: every thread re-runs its chunk from its true carry-in and writes h_t.
+// CL > 0: a chunk holds at most CL steps and the thread keeps all its inputs in registers -- every load of
+// the kernel is issued up front, one memory round trip instead of four (U was written by other XCDs a
+// moment ago, so each exposed round trip is a miss in this XCD's L2).  CL = 0: any chunk length, the
+// inputs are streamed twice.
+template <int CL>
 __global__ __launch_bounds__(SRU_CHUNKS * SRU_CHANNELS) void sru_scan_kernel(
     const float *__restrict__ U, const bf16_t *__restrict__ x_in, int L, int n_h, int k,
     const float *__restrict__ b_f, const float *__restrict__ b_r, bf16_t *__restrict__ h_out)
@@ -68,31 +73,81 @@ __global__ __launch_bounds__(SRU_CHUNKS * SRU_CHANNELS) void sru_scan_kernel(
     const int t0 = q * cl < L ? q * cl : L, t1 = (t0 + cl < L) ? t0 + cl : L;
     const float bf = b_f ? b_f[j] : 0.f, br = b_r ? b_r[j] : 0.f;
     const float *u = U + (size_t)b * L * ncol + j;
+    const bf16_t *xi = x_in + (size_t)b * L * n_h + j;   // only read when k == 3 (n_in == n_h)
+    bf16_t *ho = h_out + (size_t)b * L * n_h + j;
+
+    constexpr int NR = CL > 0 ? CL : 1;
+    float ux[NR], uf[NR], ur[NR], uh[NR];
+    if (CL > 0) {
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            const int t = t0 + i;
+            const bool ok = t < t1;
+            const float *ut = u + (size_t)(ok ? t : t0) * ncol;
+            ux[i] = ok ? ut[0] : 0.f;
+            uf[i] = ok ? ut[n_h] : 0.f;
+            ur[i] = ok ? ut[2 * n_h] : 0.f;
+            uh[i] = !ok ? 0.f : (k == 4 ? ut[3 * n_h] : bf16_to_f32(xi[(size_t)t * n_h]));
+        }
+    }
 
     float a = 1.f, c = 0.f;
+    if (CL > 0) {
+#pragma unroll
+        for (int i = 0; i < NR; ++i)
+            if (t0 + i < t1) {
+                const float f = sigmoidf_(uf[i] + bf);
+                uf[i] = f;                               // the gate itself from here on
+                a *= f;
+                c = f * c + (1.f - f) * ux[i];
+            }
+    } else {
 #pragma unroll 4
-    for (int t = t0; t < t1; ++t) {
-        const float *ut = u + (size_t)t * ncol;
-        float f = sigmoidf_(ut[n_h] + bf);
-        a *= f;
-        c = f * c + (1.f - f) * ut[0];
+        for (int t = t0; t < t1; ++t) {
+            const float *ut = u + (size_t)t * ncol;
+            float f = sigmoidf_(ut[n_h] + bf);
+            a *= f;
+            c = f * c + (1.f - f) * ut[0];
+        }
     }
     carry_a[q][ch] = a;
     carry_b[q][ch] = c;
     __syncthreads();
-    if (q == 0) {   // carry-in of every chunk of this channel, in place: carry_b[p] <- state entering chunk p
-        float run = 0.f;
-        for (int p = 0; p < SRU_CHUNKS; ++p) {
-            float na = carry_a[p][ch], nb = carry_b[p][ch];
-            carry_b[p][ch] = run;
-            run = na * run + nb;
+    // Carry-in of every chunk, in place (carry_b[p] <- state entering chunk p): the 64 chunk maps
+    // c -> a c + b of a channel are composed by an inclusive scan across the 64 lanes of one wavefront
+    // (wavefront w takes channel w; six doubling steps instead of a serial chain of 64 LDS round trips,
+    // which was ~40 % of this kernel's time)
+    {
+        const int lane = threadIdx.x & 63, sc = threadIdx.x >> 6;      // lane = chunk, sc = channel
+        float pa = carry_a[lane][sc], pb = carry_b[lane][sc];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const float qa = __shfl_up(pa, o, 64), qb = __shfl_up(pb, o, 64);   // the map of the chunks before
+            if (lane >= o) {
+                pb = pa * qb + pb;       // (this) o (earlier): c -> pa (qa c + qb) + pb
+                pa = pa * qa;
+            }
         }
+        // state after chunks 0..lane from c = 0 is pb; chunk lane + 1 starts from it
+        const float into_next = pb;
+        const float mine = __shfl_up(into_next, 1, 64);
+        __syncthreads();                 // every (a, b) has been read before any carry is overwritten
+        carry_b[lane][sc] = lane == 0 ? 0.f : mine;
     }
     __syncthreads();
     c = carry_b[q][ch];
 
-    const bf16_t *xi = x_in + (size_t)b * L * n_h + j;   // only read when k == 3 (n_in == n_h)
-    bf16_t *ho = h_out + (size_t)b * L * n_h + j;
+    if (CL > 0) {
+#pragma unroll
+        for (int i = 0; i < NR; ++i)
+            if (t0 + i < t1) {
+                const float f = uf[i];
+                const float r = sigmoidf_(ur[i] + br);
+                c = f * c + (1.f - f) * ux[i];
+                ho[(size_t)(t0 + i) * n_h] = f32_to_bf16(r * tanhf_(c) + (1.f - r) * uh[i]);
+            }
+        return;
+    }
 #pragma unroll 4
     for (int t = t0; t < t1; ++t) {
         const float *ut = u + (size_t)t * ncol;
@@ -205,7 +260,9 @@ extern "C" int sru_predict(const void *emb, const sru_weights *w, int B, int L, 
                            (const bf16_t *)wl, T, nin, ncol, U);
         MOE_CHECK_LAUNCH("sru_predict/proj");
         bf16_t *out = hbuf[l & 1];
-        hipLaunchKernelGGL(sru_scan_kernel, dim3(n_h / SRU_CHANNELS, B), dim3(SRU_CHUNKS * SRU_CHANNELS), 0, st, U, cur, L,
+        const int chunk_len = ceil_div(L, SRU_CHUNKS);
+        auto scan = chunk_len <= 8 ? sru_scan_kernel<8> : chunk_len <= 16 ? sru_scan_kernel<16> : sru_scan_kernel<0>;
+        hipLaunchKernelGGL(scan, dim3(n_h / SRU_CHANNELS, B), dim3(SRU_CHUNKS * SRU_CHANNELS), 0, st, U, cur, L,
                            n_h, k,
                            w->b_f ? w->b_f[l] : nullptr, w->b_r ? w->b_r[l] : nullptr, out);
         MOE_CHECK_LAUNCH("sru_predict/scan");

@@ -46,6 +46,7 @@ def _compare(moe, s, what):
     (5, 513, 192, 128, 1, 256, 0.2),   # L not a multiple of the chunk count
     (1, 1, 128, 128, 1, 8, 0.1),
     (4, 128, 256, 128, 10, 128, 0.1),  # the depth the paper uses (10 layers)
+    (2, 1500, 128, 128, 2, 8, 0.1),    # chunks longer than the register-resident scan holds
 ])
 def test_sru_small(B, L, n_in, n_h, layers, n_out, bias):
     import paper_2605_11537_amd as moe
