@@ -49,7 +49,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *
                                                                   float *__restrict__ logits_opt)
 {
     constexpr int E = NB * 128;
-    constexpr int LDL = E + 4;
+    constexpr int LDL = E + 8;                    // 8 threads per row, 4 rows per half wavefront: bank 8 r + sub
     constexpr int RT_BM = MB * 32;
     constexpr int BK = MB == 4 ? 64 : RT_BK;      // keeps the staging buffers under 64 KB
     constexpr int STAGE_BYTES = gemm_lds_elems<MB, BK>() * 2, TILE_BYTES = 32 * LDL * 4;
@@ -76,12 +76,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *
             for (int v = 0; v < 16; ++v)
                 tile[acc_row(v, lane) * LDL + (w * NB + nb) * 32 + (lane & 31)] = acc[mb][nb][v] + b[nb];
         __syncthreads();
-        // 8 threads per row, each over E/8 strided columns, then a 3-step butterfly
+        // 8 threads per row, each over E/8 strided columns held in registers (one batch of independent LDS
+        // reads: read one by one inside the loops below, every read was a full LDS round trip in a
+        // dependent chain, and this step took as long as the product), then a 3-step butterfly
         const int r = tid >> 3, sub = tid & 7;
         const float *row = tile + r * LDL;
-        float best = row[sub];
+        constexpr int PER = E / 8;
+        float lv[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) lv[i] = row[sub + 8 * i];
+        float best = lv[0];
         int bi = sub;
-        for (int c = sub + 8; c < E; c += 8) argmax_merge(best, bi, row[c], c);
+#pragma unroll
+        for (int i = 1; i < PER; ++i) argmax_merge(best, bi, lv[i], sub + 8 * i);
 #pragma unroll
         for (int o = 1; o < 8; o <<= 1) {
             float ov = __shfl_xor(best, o, 64);
@@ -89,7 +96,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *
             argmax_merge(best, bi, ov, oi);
         }
         float z = 0.f;
-        for (int c = sub; c < E; c += 8) z += expf(row[c] - best);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) z += expf(lv[i] - best);
 #pragma unroll
         for (int o = 1; o < 8; o <<= 1) z += __shfl_xor(z, o, 64);
         const int grow = row0 + mb * 32 + r;
@@ -111,8 +119,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *
                 if (j < top_k) {
                     float v = -INFINITY;
                     int vi = 0x7fffffff;
-                    for (int c = sub; c < E; c += 8) {
-                        const float t = row[c];
+#pragma unroll
+                    for (int i = 0; i < PER; ++i) {
+                        const float t = lv[i];
+                        const int c = sub + 8 * i;
                         if (t < pv || (t == pv && c > pi)) argmax_merge(v, vi, t, c);
                     }
 #pragma unroll
