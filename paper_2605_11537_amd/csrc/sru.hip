@@ -159,6 +159,194 @@ __global__ __launch_bounds__(SRU_CHUNKS * SRU_CHANNELS) void sru_scan_kernel(
     }
 }
 
+// ------------------------------------------------------------------ one SRU layer in one kernel (L <= 512)
+// Workgroup (channel block cb of 8 channels, sequence b): the projections of ITS 8 channels for all L
+// positions -- 32 columns of [W | W_f | W_r | (W_h)], one matrix-core column block, gathered from the packed
+// image piece by piece -- land in LDS (L x 32 binary32), and the recurrence runs from there: time chunks
+// x 8 channels (64 chunks), chunk maps composed by a doubling scan across the chunks, every chunk re-run from its true
+// carry-in.  The projections never go to memory (the two-kernel form writes and re-reads 3-4 binary32
+// values per position and channel, and its scan was bound by what one CU can fetch), there is one launch per
+// layer instead of two, and B * n_h / 8 workgroups cover the chip at 8 sequences x 256 channels.
+// The token rows reach the matrix cores without a workgroup barrier (whole lines from memory, a
+// wavefront-private LDS transposition, see below).
+constexpr int FUS_CH = 8;              // channels per workgroup
+constexpr int FUS_THREADS = 512;       // 8 wavefronts: 2 per SIMD, so one's loads fly under the other's work
+constexpr int FUS_CHUNKS = FUS_THREADS / FUS_CH;   // 64 time chunks per sequence
+constexpr int FUS_MAX_L = 512;
+constexpr int FUS_CL = FUS_MAX_L / FUS_CHUNKS;     // steps per chunk at most
+constexpr int FUS_LDU = 33;            // row stride of the LDS tile, binary32 elements
+constexpr int FUS_KC = 64;             // k per register buffer
+
+template <int NRB>                     // 32-row blocks per wavefront: L <= 256 * NRB
+__global__ __launch_bounds__(FUS_THREADS, 1) void sru_layer_fused_kernel(const bf16_t *__restrict__ X,
+                                                                         const bf16_t *__restrict__ Wp, int L, int K,
+                                                                         int n_h, int kgates,
+                                                                         const float *__restrict__ b_f,
+                                                                         const float *__restrict__ b_r,
+                                                                         bf16_t *__restrict__ h_out)
+{
+    // the L x 32 tile of projections; during the product, the wavefronts' staging pieces for the token rows
+    constexpr int TILE_FLOATS = FUS_MAX_L * FUS_LDU, STAGE_FLOATS = (FUS_THREADS / 64) * NRB * 32 * (FUS_KC + 8) / 2;
+    __shared__ __attribute__((aligned(16))) float u_lds[TILE_FLOATS > STAGE_FLOATS ? TILE_FLOATS : STAGE_FLOATS];
+    __shared__ float car_a[2][FUS_CHUNKS][FUS_CH], car_b[2][FUS_CHUNKS][FUS_CH];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    // Workgroup i runs on XCD i % 8.  All channel blocks of a sequence read the same token rows, written a
+    // moment ago by other XCDs: with whole sequences per XCD (sequence b on XCD b % 8, when their number
+    // allows) an XCD's L2 fetches 1/8 of the rows instead of all of them.
+    int cb, b;
+    {
+        const int ncb = n_h / FUS_CH, nseq = gridDim.x / ncb;
+        if (nseq % 8 == 0) {
+            const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+            b = xcd + 8 * (slot / ncb);
+            cb = slot % ncb;
+        } else {
+            b = blockIdx.x / ncb;
+            cb = blockIdx.x % ncb;
+        }
+    }
+    const int KG = K >> 3;
+    // recurrence roles: thread = (chunk q, channel ch)
+    const int ch = tid & (FUS_CH - 1), q = tid / FUS_CH;
+    const int j = cb * FUS_CH + ch;
+    const int cl = (L + FUS_CHUNKS - 1) / FUS_CHUNKS;
+    const int t0 = q * cl < L ? q * cl : L, t1 = t0 + cl < L ? t0 + cl : L;
+    // highway input when the widths are equal (K == n_h): fetched now, used at the very end
+    float hwv[FUS_CL];
+    if (kgates == 3) {
+        const bf16_t *xi = X + (size_t)b * L * K + j;
+#pragma unroll
+        for (int i = 0; i < FUS_CL; ++i) hwv[i] = t0 + i < t1 ? bf16_to_f32(xi[(size_t)(t0 + i) * K]) : 0.f;
+    }
+    // ---- projections: U[t][c], c = gate * 8 + channel
+    {
+        // Token rows: a wavefront fetches its own row blocks in whole 128-byte lines (8 lanes per row, 8 rows
+        // per load), turns them into A fragments through a private piece of LDS (row stride 72 elements, no
+        // barrier: LDS operations of one wavefront execute in order), three register buffers deep.  A lane
+        // loading its fragment straight from memory touches 32 bytes of 32 different lines per load, and
+        // the kernel was bound by those transactions.
+        constexpr int LDA = FUS_KC + 8;
+        bf16_t *stage = reinterpret_cast<bf16_t *>(u_lds) + (size_t)w * (NRB * 32 * LDA);
+        const int r = lane & 31, kh = lane >> 5;
+        const int lrow = lane >> 3, lpiece = lane & 7;
+        const bf16_t *a_ptr[NRB][4];
+        bool a_ok[NRB][4];
+#pragma unroll
+        for (int i = 0; i < NRB; ++i)
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) {
+                const int t = (w + 8 * i) * 32 + sb * 8 + lrow;   // row blocks dealt to the eight wavefronts in turn
+                a_ok[i][sb] = t < L;
+                a_ptr[i][sb] = X + ((size_t)b * L + (a_ok[i][sb] ? t : 0)) * K + lpiece * 8;
+            }
+        const int gate = r >> 3, chn = r & 7;
+        const bool b_ok = gate < kgates;
+        const int col = (b_ok ? gate : 0) * n_h + cb * FUS_CH + chn;
+        const uint4 *b_ptr = reinterpret_cast<const uint4 *>(Wp) + ((size_t)(col >> 5) * KG + kh) * 32 + (col & 31);
+        f32x16_t acc[NRB][1];
+        zero_acc<NRB, 1>(acc);
+        constexpr int KS = FUS_KC / 16;
+        uint4 ga[3][NRB][4], fb[3][KS];
+        auto load = [&](int kc, int buf) {
+            const int k0 = kc * FUS_KC;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                fb[buf][ks] = b_ok ? b_ptr[(size_t)((k0 >> 3) + ks * 2) * 32] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < NRB; ++i)
+#pragma unroll
+                for (int sb = 0; sb < 4; ++sb)
+                    ga[buf][i][sb] =
+                        a_ok[i][sb] ? *reinterpret_cast<const uint4 *>(a_ptr[i][sb] + k0) : make_uint4(0, 0, 0, 0);
+        };
+        auto compute = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < NRB; ++i)
+#pragma unroll
+                for (int sb = 0; sb < 4; ++sb)
+                    *reinterpret_cast<uint4 *>(stage + (i * 32 + sb * 8 + lrow) * LDA + lpiece * 8) = ga[buf][i][sb];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int i = 0; i < NRB; ++i) {
+                    const uint4 av = *reinterpret_cast<const uint4 *>(stage + (i * 32 + r) * LDA + ks * 16 + kh * 8);
+                    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av),
+                                                                        __builtin_bit_cast(bf16x8_t, fb[buf][ks]),
+                                                                        acc[i][0], 0, 0, 0);
+                }
+        };
+        const int nkc = K / FUS_KC;
+        load(0, 0);
+        if (nkc > 1) load(1, 1);
+        for (int kc = 0; kc < nkc; kc += 3) {
+            if (kc + 2 < nkc) load(kc + 2, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(0);
+            if (kc + 1 < nkc) {
+                if (kc + 3 < nkc) load(kc + 3, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(1);
+            }
+            if (kc + 2 < nkc) {
+                if (kc + 4 < nkc) load(kc + 4, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(2);
+            }
+        }
+        __syncthreads();           // the staging pieces alias the tile written next
+#pragma unroll
+        for (int i = 0; i < NRB; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int t = (w + 8 * i) * 32 + acc_row(v, lane);
+                if (t < FUS_MAX_L) u_lds[t * FUS_LDU + r] = acc[i][0][v];
+            }
+    }
+    __syncthreads();
+
+    // ---- recurrence
+    const float bf = b_f ? b_f[j] : 0.f, br = b_r ? b_r[j] : 0.f;
+    float a = 1.f, c = 0.f;
+#pragma unroll
+    for (int i = 0; i < FUS_CL; ++i)
+        if (t0 + i < t1) {
+            float *ut = u_lds + (t0 + i) * FUS_LDU;
+            const float f = sigmoidf_(ut[FUS_CH + ch] + bf);
+            ut[FUS_CH + ch] = f;                           // the gate itself from here on
+            a *= f;
+            c = f * c + (1.f - f) * ut[ch];
+        }
+    // inclusive doubling scan of the chunk maps c -> a c + b over the chunks of a channel
+    int cur = 0;
+#pragma unroll
+    for (int o = 1; o < FUS_CHUNKS; o <<= 1) {
+        car_a[cur][q][ch] = a;
+        car_b[cur][q][ch] = c;
+        __syncthreads();
+        if (q >= o) {
+            const float qa = car_a[cur][q - o][ch], qb = car_b[cur][q - o][ch];
+            c = a * qb + c;                                // (this) after (earlier)
+            a = a * qa;
+        }
+        cur ^= 1;
+    }
+    car_b[cur][q][ch] = c;                                 // state after chunks 0..q, starting from 0
+    __syncthreads();
+    c = q > 0 ? car_b[cur][q - 1][ch] : 0.f;
+
+    bf16_t *ho = h_out + (size_t)b * L * n_h + j;
+#pragma unroll
+    for (int i = 0; i < FUS_CL; ++i)
+        if (t0 + i < t1) {
+            const float *ut = u_lds + (t0 + i) * FUS_LDU;
+            const float f = ut[FUS_CH + ch];
+            const float r = sigmoidf_(ut[2 * FUS_CH + ch] + br);
+            c = f * c + (1.f - f) * ut[ch];
+            const float hw = kgates == 4 ? ut[3 * FUS_CH + ch] : hwv[i];
+            ho[(size_t)(t0 + i) * n_h] = f32_to_bf16(r * tanhf_(c) + (1.f - r) * hw);
+        }
+}
+
 struct SruWs {
     size_t u, h0, h1, wp, rws, prob, ht, total;
 };
@@ -256,10 +444,20 @@ extern "C" int sru_predict(const void *emb, const sru_weights *w, int B, int L, 
             if (rc != MOE_OK) return rc;
             wl = wp;
         }
+        bf16_t *out = hbuf[l & 1];
+        if (L <= FUS_MAX_L) {
+            // the whole layer in one kernel
+            auto fused = L <= 256 ? sru_layer_fused_kernel<1> : sru_layer_fused_kernel<2>;
+            hipLaunchKernelGGL(fused, dim3((n_h / FUS_CH) * B), dim3(FUS_THREADS), 0, st, cur, (const bf16_t *)wl, L, nin, n_h, k,
+                               w->b_f ? w->b_f[l] : nullptr, w->b_r ? w->b_r[l] : nullptr, out);
+            MOE_CHECK_LAUNCH("sru_predict/layer");
+            cur = out;
+            nin = n_h;
+            continue;
+        }
         hipLaunchKernelGGL(sru_proj_kernel, dim3(ceil_div(T, 64) * (ncol / 128)), dim3(GEMM_THREADS), 0, st, cur,
                            (const bf16_t *)wl, T, nin, ncol, U);
         MOE_CHECK_LAUNCH("sru_predict/proj");
-        bf16_t *out = hbuf[l & 1];
         const int chunk_len = ceil_div(L, SRU_CHUNKS);
         auto scan = chunk_len <= 8 ? sru_scan_kernel<8> : chunk_len <= 16 ? sru_scan_kernel<16> : sru_scan_kernel<0>;
         hipLaunchKernelGGL(scan, dim3(n_h / SRU_CHANNELS, B), dim3(SRU_CHUNKS * SRU_CHANNELS), 0, st, U, cur, L,
