@@ -59,13 +59,28 @@ __device__ __forceinline__ float wave_sum_f(float v) { return wave_reduce_f(v, [
 __device__ __forceinline__ float wave_max_f(float v) { return wave_reduce_f(v, [](float a, float b) { return fmaxf(a, b); }); }
 
 __global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf16_t *__restrict__ h,
-                                                                        const bf16_t *__restrict__ ht, int L, int Lp,
+                                                                        const bf16_t *__restrict__ hp, int L, int Lp,
                                                                         int n, bf16_t *__restrict__ z)
 {
     __shared__ __attribute__((aligned(16))) float s_lds[ATT_QT * ATT_LDS_S];
     __shared__ __attribute__((aligned(16))) bf16_t q_lds[ATT_QT * (ATT_MAX_N + 8)];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int seq = blockIdx.y, q0 = blockIdx.x * ATT_QT;
+    // Workgroup i runs on XCD i % 8; all query blocks of a sequence read the same keys and transposed states,
+    // so whole sequences go to one XCD (sequence b to XCD b % 8) when their number allows: an XCD's L2 then
+    // holds 1/8 of the states instead of cycling through all of them.
+    int seq, qblk;
+    {
+        const int nqb = (L + ATT_QT - 1) / ATT_QT, nseq = gridDim.x / nqb;
+        if (nseq % 8 == 0) {
+            const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+            seq = xcd + 8 * (slot / nqb);
+            qblk = slot % nqb;
+        } else {
+            seq = blockIdx.x / nqb;
+            qblk = blockIdx.x % nqb;
+        }
+    }
+    const int q0 = qblk * ATT_QT;
     const bf16_t *hs = h + (size_t)seq * L * n;
     const int ldq = n + 8;
     // query rows (positions past the sequence end repeat its last row; they are never stored)
@@ -78,27 +93,45 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf
     // 1. scores: wavefront w takes key blocks w, w+4, ...
     const float scale = rsqrtf((float)n);
     const int n_kb = (L + 31) / 32;
-    for (int kb = w; kb < n_kb; kb += 4) {
-        f32x16_t acc;
+    {
+        // the key fragments of a block are all requested at once, and those of the wavefront's next block
+        // before the current block's matrix instructions: one exposed round trip per wavefront, not per block
+        constexpr int NKS = ATT_MAX_N / 16;
+        uint4 kf[2][NKS];
+        auto load_keys = [&](int kb, int buf) {
+            const int key = kb * 32 + (lane & 31);
+            const bf16_t *krow = hs + (size_t)(key < L ? key : L - 1) * n + (lane >> 5) * 8;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-        const int key = kb * 32 + (lane & 31);
-        const bf16_t *krow = hs + (size_t)(key < L ? key : L - 1) * n + (lane >> 5) * 8;
-        const bf16_t *qrow = q_lds + (lane & 31) * ldq + (lane >> 5) * 8;
-        // all of the block's key fragments are requested before the first matrix instruction needs one
-        uint4 kf[ATT_MAX_N / 16];
+            for (int ks = 0; ks < NKS; ++ks)
+                if (ks * 16 < n) kf[buf][ks] = *reinterpret_cast<const uint4 *>(krow + ks * 16);
+        };
+        auto score_block = [&](int kb, int buf) {
+            f32x16_t acc;
 #pragma unroll
-        for (int ks = 0; ks < ATT_MAX_N / 16; ++ks)
-            if (ks * 16 < n) kf[ks] = *reinterpret_cast<const uint4 *>(krow + ks * 16);
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            const int key = kb * 32 + (lane & 31);
+            const bf16_t *qrow = q_lds + (lane & 31) * ldq + (lane >> 5) * 8;
 #pragma unroll
-        for (int ks = 0; ks < ATT_MAX_N / 16; ++ks)
-            if (ks * 16 < n) {
-                const uint4 a = *reinterpret_cast<const uint4 *>(qrow + ks * 16);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                              __builtin_bit_cast(bf16x8_t, kf[ks]), acc, 0, 0, 0);
+            for (int ks = 0; ks < NKS; ++ks)
+                if (ks * 16 < n) {
+                    const uint4 a = *reinterpret_cast<const uint4 *>(qrow + ks * 16);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                  __builtin_bit_cast(bf16x8_t, kf[buf][ks]), acc, 0, 0, 0);
+                }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s_lds[acc_row(v, lane) * ATT_LDS_S + key] = acc[v] * scale;
+        };
+        if (w < n_kb) load_keys(w, 0);
+        for (int kb = w; kb < n_kb; kb += 8) {
+            if (kb + 4 < n_kb) load_keys(kb + 4, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            score_block(kb, 0);
+            if (kb + 4 < n_kb) {
+                if (kb + 8 < n_kb) load_keys(kb + 8, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                score_block(kb + 4, 1);
             }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s_lds[acc_row(v, lane) * ATT_LDS_S + key] = acc[v] * scale;
+        }
     }
     __syncthreads();
     // 2. + 3. one wavefront per 8 rows
@@ -158,32 +191,62 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf
     // 32 rows; per step of 16 positions one weight fragment (from the score tile, rounded to bf16) and one
     // fragment of the transposed states per block.
     {
-        const bf16_t *hts = ht + (size_t)seq * n * Lp;          // [n][Lp], positions >= L are zero
+        // packed image of this sequence's states as a (positions x features) matrix, positions >= L zero:
+        // a wavefront's fragment load is 1 KB of consecutive memory
+        const uint4 *hps = reinterpret_cast<const uint4 *>(hp) + (size_t)seq * (n / 32) * (Lp / 8) * 32;
         f32x16_t acc[2];
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.f;
         const int fb0 = 2 * w;
         const bool have[2] = {fb0 * 32 < n, (fb0 + 1) * 32 < n};      // wave-uniform
         const float *arow = s_lds + (lane & 31) * ATT_LDS_S + (lane >> 5) * 8;
-        const bf16_t *b0 = hts + (size_t)(fb0 * 32 + (lane & 31)) * Lp + (lane >> 5) * 8;
-        const bf16_t *b1 = b0 + (size_t)32 * Lp;
-        for (int j0 = 0; j0 < Lp; j0 += 16) {
-            uint4 bf0 = make_uint4(0, 0, 0, 0), bf1 = make_uint4(0, 0, 0, 0);
-            if (have[0]) bf0 = *reinterpret_cast<const uint4 *>(b0 + j0);
-            if (have[1]) bf1 = *reinterpret_cast<const uint4 *>(b1 + j0);
-            const float4 a_lo = *reinterpret_cast<const float4 *>(arow + j0);
-            const float4 a_hi = *reinterpret_cast<const float4 *>(arow + j0 + 4);
-            uint4 af;
-            af.x = pack_bf16x2(a_lo.x, a_lo.y);
-            af.y = pack_bf16x2(a_lo.z, a_lo.w);
-            af.z = pack_bf16x2(a_hi.x, a_hi.y);
-            af.w = pack_bf16x2(a_hi.z, a_hi.w);
-            if (have[0])
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af),
-                                                                 __builtin_bit_cast(bf16x8_t, bf0), acc[0], 0, 0, 0);
-            if (have[1])
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af),
-                                                                 __builtin_bit_cast(bf16x8_t, bf1), acc[1], 0, 0, 0);
+        const uint4 *b0 = hps + ((size_t)fb0 * (Lp / 8) + (lane >> 5)) * 32 + (lane & 31);
+        const uint4 *b1 = b0 + (size_t)(Lp / 8) * 32;
+        // the state fragments of 8 steps (128 positions) are requested together, the next batch before the
+        // current batch's matrix instructions; fetched one step at a time, every step waited a round trip
+        constexpr int CB = 8;
+        uint4 sf[2][CB][2];
+        auto load_states = [&](int j0, int buf) {
+#pragma unroll
+            for (int u = 0; u < CB; ++u) {
+                const int j = j0 + u * 16;
+                sf[buf][u][0] = have[0] && j < Lp ? b0[(size_t)(j >> 3) * 32] : make_uint4(0, 0, 0, 0);
+                sf[buf][u][1] = have[1] && j < Lp ? b1[(size_t)(j >> 3) * 32] : make_uint4(0, 0, 0, 0);
+            }
+        };
+        auto context_batch = [&](int j0, int buf) {
+#pragma unroll
+            for (int u = 0; u < CB; ++u) {
+                const int j = j0 + u * 16;
+                if (j < Lp) {                                          // wave-uniform
+                    const float4 a_lo = *reinterpret_cast<const float4 *>(arow + j);
+                    const float4 a_hi = *reinterpret_cast<const float4 *>(arow + j + 4);
+                    uint4 af;
+                    af.x = pack_bf16x2(a_lo.x, a_lo.y);
+                    af.y = pack_bf16x2(a_lo.z, a_lo.w);
+                    af.z = pack_bf16x2(a_hi.x, a_hi.y);
+                    af.w = pack_bf16x2(a_hi.z, a_hi.w);
+                    if (have[0])
+                        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af),
+                                                                         __builtin_bit_cast(bf16x8_t, sf[buf][u][0]),
+                                                                         acc[0], 0, 0, 0);
+                    if (have[1])
+                        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, af),
+                                                                         __builtin_bit_cast(bf16x8_t, sf[buf][u][1]),
+                                                                         acc[1], 0, 0, 0);
+                }
+            }
+        };
+        load_states(0, 0);
+        for (int j0 = 0; j0 < Lp; j0 += 2 * CB * 16) {
+            if (j0 + CB * 16 < Lp) load_states(j0 + CB * 16, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            context_batch(j0, 0);
+            if (j0 + CB * 16 < Lp) {
+                if (j0 + 2 * CB * 16 < Lp) load_states(j0 + 2 * CB * 16, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                context_batch(j0 + CB * 16, 1);
+            }
         }
 #pragma unroll
         for (int k = 0; k < 2; ++k)
@@ -199,22 +262,24 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf
     }
 }
 
-// h [B*L, n] -> ht [B][n][Lp] (positions contiguous, zero beyond L): 32 x 32 tiles through LDS
-__global__ __launch_bounds__(256) void sru_transpose_states_kernel(const bf16_t *__restrict__ h, int L, int Lp, int n,
-                                                                   bf16_t *__restrict__ ht)
+// h [B*L, n] -> per sequence the packed image of the (Lp x n) matrix of its states (positions past L are
+// zero): 16-byte piece ((f / 32) * (Lp / 8) + t / 8) * 32 + f % 32 holds h[8 (t / 8) .. + 7][f]
+__global__ __launch_bounds__(256) void sru_pack_states_kernel(const bf16_t *__restrict__ h, int L, int Lp, int n,
+                                                              uint4 *__restrict__ hp)
 {
-    __shared__ bf16_t tile[32][33];
-    const int seq = blockIdx.z, t0 = blockIdx.x * 32, f0 = blockIdx.y * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    for (int r = ty; r < 32; r += 8) {
-        const int t = t0 + r;
-        tile[r][tx] = t < L ? h[((size_t)seq * L + t) * n + f0 + tx] : (bf16_t)0;
+    const int per_seq = (n / 32) * (Lp / 8) * 32;
+    const int p = blockIdx.x * 256 + threadIdx.x, seq = blockIdx.y;
+    if (p >= per_seq) return;
+    const int c = p & 31, kg = (p >> 5) % (Lp / 8), strip = (p >> 5) / (Lp / 8);
+    const bf16_t *src = h + ((size_t)seq * L + kg * 8) * n + strip * 32 + c;
+    uint32_t v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int t = kg * 8 + 2 * i;
+        const uint32_t lo = t < L ? src[(size_t)(2 * i) * n] : 0, hi = t + 1 < L ? src[(size_t)(2 * i + 1) * n] : 0;
+        v[i] = lo | (hi << 16);
     }
-    __syncthreads();
-    for (int r = ty; r < 32; r += 8) {
-        const int t = t0 + tx;
-        if (t < Lp) ht[((size_t)seq * n + f0 + r) * Lp + t] = tile[tx][r];
-    }
+    hp[(size_t)seq * per_seq + p] = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
 size_t sru_attention_ws_bytes(int B, int L, int n) { return align_up((size_t)(B > 0 ? B : 1) * n * align_up((size_t)L, 16) * 2, 256); }
@@ -226,10 +291,10 @@ int sru_attention_launch(const void *h, int B, int L, int n, void *z, void *ht_w
                 ATT_MAX_L, ATT_MAX_N, L, n);
     if (B == 0) return MOE_OK;
     const int Lp = (int)align_up((size_t)L, 16);
-    hipLaunchKernelGGL(sru_transpose_states_kernel, dim3(ceil_div(Lp, 32), n / 32, B), dim3(256), 0, st, (const bf16_t *)h, L,
-                       Lp, n, (bf16_t *)ht_ws);
+    hipLaunchKernelGGL(sru_pack_states_kernel, dim3(ceil_div((n / 32) * (Lp / 8) * 32, 256), B), dim3(256), 0, st,
+                       (const bf16_t *)h, L, Lp, n, (uint4 *)ht_ws);
     MOE_CHECK_LAUNCH(who);
-    hipLaunchKernelGGL(sru_attention_kernel, dim3(ceil_div(L, ATT_QT), B), dim3(GEMM_THREADS), 0, st, (const bf16_t *)h,
+    hipLaunchKernelGGL(sru_attention_kernel, dim3(ceil_div(L, ATT_QT) * B), dim3(GEMM_THREADS), 0, st, (const bf16_t *)h,
                        (const bf16_t *)ht_ws, L, Lp, n, (bf16_t *)z);
     MOE_CHECK_LAUNCH(who);
     return MOE_OK;

@@ -40,18 +40,18 @@ typedef unsigned short bf16_t;  // raw bits
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
 // round to nearest, ties to even; NaN kept quiet
-__device__ __forceinline__ bf16_t f32_to_bf16(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
-}
+// binary32 -> bf16, round to nearest even, by the hardware conversion (v_cvt_pk_bf16_f32: one instruction
+// per pair; the same rounding spelled out in integer operations is seven per value)
+typedef float moe_f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 moe_bf16x2_t __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    const moe_f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, moe_bf16x2_t));
 }
+
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 // XCD-aware remap of a linear workgroup id.  Hardware deals consecutive workgroup ids to the
 // 8 XCDs in turn, so ids congruent mod 8 share an L2.  The n_valid units of work are cut into 8
