@@ -10,7 +10,7 @@
 //      operand fragment the matrix instruction wants (8 consecutive features per lane), so keys are
 //      read straight from global memory (the sequence's states stay in L2 for its 16 workgroups);
 //      the 32 x L fp32 score tile is kept in LDS.
-//   2. sparsemax per row, one wavefront per 8 rows, each lane holding L/64 scores: tau by Michelot's
+//   2. sparsemax per row, one wavefront per 4 rows, each lane holding L/64 scores: tau by Michelot's
 //      fixed point (tau = (sum of the entries above tau - 1) / their count, until the set is stable),
 //      which ends at exactly the support the sorting definition gives.
 //   3. the context sum_j a[t, j] h_j on the matrix cores: the contraction runs over positions, so the
@@ -27,6 +27,8 @@ namespace moe {
 constexpr int ATT_QT = 32;           // query rows per workgroup
 constexpr int ATT_MAX_L = 1024;      // positions per sequence the LDS score tile holds
 constexpr int ATT_MAX_N = 256;       // features per state
+constexpr int ATT_WAVES = 8;         // wavefronts per workgroup (two per SIMD)
+constexpr int ATT_THREADS = ATT_WAVES * 64;
 constexpr int ATT_LDS_S = ATT_MAX_L + 4;
 
 // Wavefront-wide reductions on the data-parallel-primitive path (a cross-lane operand of an ordinary
@@ -58,7 +60,7 @@ __device__ __forceinline__ float wave_reduce_f(float v, Op op)
 __device__ __forceinline__ float wave_sum_f(float v) { return wave_reduce_f(v, [](float a, float b) { return a + b; }); }
 __device__ __forceinline__ float wave_max_f(float v) { return wave_reduce_f(v, [](float a, float b) { return fmaxf(a, b); }); }
 
-__global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf16_t *__restrict__ h,
+__global__ __launch_bounds__(ATT_THREADS, 1) void sru_attention_kernel(const bf16_t *__restrict__ h,
                                                                         const bf16_t *__restrict__ hp, int L, int Lp,
                                                                         int n, bf16_t *__restrict__ z)
 {
@@ -84,13 +86,13 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf
     const bf16_t *hs = h + (size_t)seq * L * n;
     const int ldq = n + 8;
     // query rows (positions past the sequence end repeat its last row; they are never stored)
-    for (int p = tid; p < ATT_QT * (n / 8); p += GEMM_THREADS) {
+    for (int p = tid; p < ATT_QT * (n / 8); p += ATT_THREADS) {
         const int r = p / (n / 8), c8 = p % (n / 8);
         const int t = q0 + r < L ? q0 + r : L - 1;
         *reinterpret_cast<uint4 *>(q_lds + r * ldq + c8 * 8) = *reinterpret_cast<const uint4 *>(hs + (size_t)t * n + c8 * 8);
     }
     __syncthreads();
-    // 1. scores: wavefront w takes key blocks w, w+4, ...
+    // 1. scores: wavefront w takes key blocks w, w+8, ...
     const float scale = rsqrtf((float)n);
     const int n_kb = (L + 31) / 32;
     {
@@ -122,23 +124,23 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf
             for (int v = 0; v < 16; ++v) s_lds[acc_row(v, lane) * ATT_LDS_S + key] = acc[v] * scale;
         };
         if (w < n_kb) load_keys(w, 0);
-        for (int kb = w; kb < n_kb; kb += 8) {
-            if (kb + 4 < n_kb) load_keys(kb + 4, 1);
+        for (int kb = w; kb < n_kb; kb += 2 * ATT_WAVES) {
+            if (kb + ATT_WAVES < n_kb) load_keys(kb + ATT_WAVES, 1);
             __builtin_amdgcn_sched_barrier(0);
             score_block(kb, 0);
-            if (kb + 4 < n_kb) {
-                if (kb + 8 < n_kb) load_keys(kb + 8, 0);
+            if (kb + ATT_WAVES < n_kb) {
+                if (kb + 2 * ATT_WAVES < n_kb) load_keys(kb + 2 * ATT_WAVES, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                score_block(kb + 4, 1);
+                score_block(kb + ATT_WAVES, 1);
             }
         }
     }
     __syncthreads();
-    // 2. + 3. one wavefront per 8 rows
+    // 2. + 3. one wavefront per 4 rows
     constexpr int PER = ATT_MAX_L / 64;
     const int n_chunks = (L + 63) / 64;
-    for (int rr = 0; rr < ATT_QT / 4; ++rr) {
-        const int r = w * (ATT_QT / 4) + rr;
+    for (int rr = 0; rr < ATT_QT / ATT_WAVES; ++rr) {
+        const int r = w * (ATT_QT / ATT_WAVES) + rr;
         const int t = q0 + r;
         if (t >= L) {                      // wave-uniform; the matrix product below reads all 32 weight rows
             for (int j = lane; j < Lp; j += 64) s_lds[r * ATT_LDS_S + j] = 0.f;
@@ -187,7 +189,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf
             if (i < n_chunks && i * 64 + lane < Lp) s_lds[r * ATT_LDS_S + i * 64 + lane] = zr[i] > tau ? zr[i] - tau : 0.f;
     }
     __syncthreads();   // every row's weights are in the score tile
-    // 3. context on the matrix cores: wavefront w owns feature blocks 2w and 2w+1 (32 features each) of all
+    // 3. context on the matrix cores: wavefront w owns feature block w (32 features; and w + 8) of all
     // 32 rows; per step of 16 positions one weight fragment (from the score tile, rounded to bf16) and one
     // fragment of the transposed states per block.
     {
@@ -197,11 +199,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf
         f32x16_t acc[2];
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[0][v] = acc[1][v] = 0.f;
-        const int fb0 = 2 * w;
-        const bool have[2] = {fb0 * 32 < n, (fb0 + 1) * 32 < n};      // wave-uniform
+        // wavefront w owns feature blocks w and w + ATT_WAVES (32 features each)
+        const int fb0 = w;
+        const bool have[2] = {fb0 * 32 < n, (fb0 + ATT_WAVES) * 32 < n};      // wave-uniform
         const float *arow = s_lds + (lane & 31) * ATT_LDS_S + (lane >> 5) * 8;
         const uint4 *b0 = hps + ((size_t)fb0 * (Lp / 8) + (lane >> 5)) * 32 + (lane & 31);
-        const uint4 *b1 = b0 + (size_t)(Lp / 8) * 32;
+        const uint4 *b1 = b0 + (size_t)ATT_WAVES * (Lp / 8) * 32;
         // the state fragments of 8 steps (128 positions) are requested together, the next batch before the
         // current batch's matrix instructions; fetched one step at a time, every step waited a round trip
         constexpr int CB = 8;
@@ -251,7 +254,7 @@ __global__ __launch_bounds__(GEMM_THREADS, 1) void sru_attention_kernel(const bf
 #pragma unroll
         for (int k = 0; k < 2; ++k)
             if (have[k]) {
-                const int f = (fb0 + k) * 32 + (lane & 31);
+                const int f = (fb0 + k * ATT_WAVES) * 32 + (lane & 31);
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int r = acc_row(v, lane);
@@ -294,7 +297,7 @@ int sru_attention_launch(const void *h, int B, int L, int n, void *z, void *ht_w
     hipLaunchKernelGGL(sru_pack_states_kernel, dim3(ceil_div((n / 32) * (Lp / 8) * 32, 256), B), dim3(256), 0, st,
                        (const bf16_t *)h, L, Lp, n, (uint4 *)ht_ws);
     MOE_CHECK_LAUNCH(who);
-    hipLaunchKernelGGL(sru_attention_kernel, dim3(ceil_div(L, ATT_QT) * B), dim3(GEMM_THREADS), 0, st, (const bf16_t *)h,
+    hipLaunchKernelGGL(sru_attention_kernel, dim3(ceil_div(L, ATT_QT) * B), dim3(ATT_THREADS), 0, st, (const bf16_t *)h,
                        (const bf16_t *)ht_ws, L, Lp, n, (bf16_t *)z);
     MOE_CHECK_LAUNCH(who);
     return MOE_OK;
