@@ -45,6 +45,10 @@ def _to_dev(a):
 
 def _workload(name):
     import synth
+    if name == "cfg1":
+        # the small fp32 case the oracle evaluates whole in milliseconds: cache-resident, launch-latency bound
+        c = synth.config_inputs(1)
+        return c, c["C"], "tiny fp32 layer T=512 d=64 F=256 E=8 C=80 R=4 Zipf(1.2) (cache-resident; latency only)"
     if name == "cfg2":
         c = synth.config_inputs(2)
         return c, c["C"], "Switch-base-128 layer T=4096 d=768 F=3072 E=128 CF=1.25 R=16 Zipf(1.0)"
@@ -156,12 +160,18 @@ def main():
 
     c, C, desc = _workload(a.workload)
     T, d, F, E, R = c["T"], c["d"], c["F"], c["E"], c["R"]
-    dt = torch.bfloat16
+    fp32 = c["x"].dtype == np.float32
+    dt = torch.float32 if fp32 else torch.bfloat16
     x, b = _to_dev(c["x"]), _to_dev(c["b_router"])
-    # static weights are packed once, outside the timed region (router included)
-    wr = moe.moe_pack_weights(_to_dev(c["w_router"])[None].contiguous())[0]
-    w1 = moe.moe_pack_weights(_to_dev(c["w1"]))
-    w2 = moe.moe_pack_weights(_to_dev(c["w2"]))
+    if fp32:
+        wr, w1, w2 = _to_dev(c["w_router"]), _to_dev(c["w1"]), _to_dev(c["w2"])
+        RL = moe.LAYOUT_PLAIN
+    else:
+        # static weights are packed once, outside the timed region (router included)
+        wr = moe.moe_pack_weights(_to_dev(c["w_router"])[None].contiguous())[0]
+        w1 = moe.moe_pack_weights(_to_dev(c["w1"]))
+        w2 = moe.moe_pack_weights(_to_dev(c["w2"]))
+        RL = moe.LAYOUT_PACKED
     torch.cuda.synchronize()
 
     top_k = c.get("top_k", 1)
@@ -196,16 +206,16 @@ def main():
             moe.set_ffn_timing_events(*evs[it["i"]])
             it["i"] += 1
         if plan_ids is None:
-            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED)
+            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL)
         else:
-            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED,
+            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL,
                           plan_ids=plan_ids)
 
     def step_off_same_plan():
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=moe.LAYOUT_PACKED)
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=RL)
 
     def step_off_budget0():
-        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED)
+        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL)
 
     for _ in range(a.warmup):
         step_on()
@@ -223,7 +233,7 @@ def main():
     K = int(kept.sum())
     active = int((kept > 0).sum())
     n_slots = int(layer.plan_out["n_slots"].item())
-    esz = 2
+    esz = 4 if fp32 else 2
     bytes_g1 = active * d * F * esz + K * d * esz + K * F * esz
     bytes_g2 = active * F * d * esz + K * F * esz + K * d * esz
     flops = 2.0 * K * d * F
@@ -262,7 +272,7 @@ def main():
 
         def step_pipelined():
             pipe.predict(sru[0])
-            pipe.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=moe.LAYOUT_PACKED)
+            pipe.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL)
 
         for _ in range(a.warmup):
             step_pipelined()
@@ -297,7 +307,7 @@ def main():
     line = {
         "metric": "MoE-layer tokens/sec (route+dispatch+FFN+combine)", "value": modes["on"], "unit": "tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_on, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if fp32 else "bf16", "data": "synthetic",
         "config": {"workload": desc, "name": a.workload, "T": T, "d_model": d, "d_ff": F, "experts": E,
                    "top_k": top_k, "slot_capacity": C, "replica_budget": R, "kept_tokens": K, "active_experts": active,
                    "slots": n_slots, "replication": "on (slot schedule)"},
