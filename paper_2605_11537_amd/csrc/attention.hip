@@ -14,8 +14,10 @@
 //      fixed point (tau = (sum of the entries above tau - 1) / their count, until the set is stable),
 //      which ends at exactly the support the sorting definition gives.
 //   3. the context sum_j a[t, j] h_j on the matrix cores: the contraction runs over positions, so the
-//      state operand must have positions contiguous -- a small kernel writes the transposed states
-//      h^T [n, L] per sequence first.  The weights go back into the score tile and are read from there
+//      state operand must have 8 consecutive positions of one feature per lane -- a small kernel first
+//      writes, per sequence, the packed image of its states as a (positions x features) matrix (the
+//      layout moe_pack_weights gives weights: a wavefront's fragment load is 1 KB of consecutive memory).
+//      The weights go back into the score tile and are read from there
 //      as the other operand, rounded to bf16 (relative error 2^-9 per weight, the size of the bf16
 //      rounding of z itself).  On the vector units the same sum is 16384 multiply-adds per lane and took
 //      three times as long as everything else in the kernel.
@@ -67,7 +69,7 @@ __global__ __launch_bounds__(ATT_THREADS, 1) void sru_attention_kernel(const bf1
     __shared__ __attribute__((aligned(16))) float s_lds[ATT_QT * ATT_LDS_S];
     __shared__ __attribute__((aligned(16))) bf16_t q_lds[ATT_QT * (ATT_MAX_N + 8)];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    // Workgroup i runs on XCD i % 8; all query blocks of a sequence read the same keys and transposed states,
+    // Workgroup i runs on XCD i % 8; all query blocks of a sequence read the same keys and packed states,
     // so whole sequences go to one XCD (sequence b to XCD b % 8) when their number allows: an XCD's L2 then
     // holds 1/8 of the states instead of cycling through all of them.
     int seq, qblk;
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(ATT_THREADS, 1) void sru_attention_kernel(const bf1
     __syncthreads();   // every row's weights are in the score tile
     // 3. context on the matrix cores: wavefront w owns feature block w (32 features; and w + 8) of all
     // 32 rows; per step of 16 positions one weight fragment (from the score tile, rounded to bf16) and one
-    // fragment of the transposed states per block.
+    // fragment of the packed states per block.
     {
         // packed image of this sequence's states as a (positions x features) matrix, positions >= L zero:
         // a wavefront's fragment load is 1 KB of consecutive memory

@@ -11,7 +11,7 @@ int route_launch(const void *x, const void *w_router, int w_layout, const float 
 // in [K][N] bf16 row-major -> packed image (N a multiple of 32), 16-byte piece ((n/32)*(K/8) + k/8)*32 + n%32
 int pack_matrix_launch(const void *in, int K, int N, void *out, hipStream_t st, const char *who);
 // attention.hip: z = h + sparsemax-attention context over each of the B sequences of L states (bf16, n features)
-size_t sru_attention_ws_bytes(int B, int L, int n);   // transposed states
+size_t sru_attention_ws_bytes(int B, int L, int n);   // packed image of the states
 int sru_attention_launch(const void *h, int B, int L, int n, void *z, void *ht_ws, hipStream_t st, const char *who);
 // plan.hip: histograms of ids in blocks of plan_partial_block() ids, partial[b][E]
 int plan_partial_block();

@@ -8,8 +8,10 @@
 // of one sequence and cuts the time axis into 64 chunks; every thread first composes its
 // chunk into (A, B) with c_out = A c_in + B, the carries are chained through LDS, and each
 // thread then re-runs its chunk from its true carry-in and writes h_t (B * n_h * 64 threads,
-// enough to cover the chip at 8 sequences x 256 channels).  The head is a router-shaped
-// product + argmax and reuses that kernel.  Static weights may arrive already packed
+// enough to cover the chip at 8 sequences x 256 channels).  For sequences of up to 512 positions steps (2)
+// and (3) are one kernel per layer with the projections kept in LDS (sru_layer_fused_kernel below); the
+// two-kernel form serves longer sequences.  The head is a router-shaped product + argmax and reuses that
+// kernel.  Static weights may arrive already packed
 // (sru_weights.w_layout), which removes the per-call re-layout kernels.
 #include "gemm_bf16.h"
 #include "route.h"
