@@ -47,6 +47,8 @@ def _compare(moe, s, what):
     (1, 1, 128, 128, 1, 8, 0.1),
     (4, 128, 256, 128, 10, 128, 0.1),  # the depth the paper uses (10 layers)
     (2, 1500, 128, 128, 2, 8, 0.1),    # chunks longer than the register-resident scan holds
+    (8, 96, 128, 256, 2, 8, 0.1),      # a multiple of 8 sequences: whole sequences per XCD in the layer kernel
+    (16, 40, 64, 128, 1, 24, 0.0),
 ])
 def test_sru_small(B, L, n_in, n_h, layers, n_out, bias):
     import paper_2605_11537_amd as moe
@@ -59,6 +61,7 @@ def test_sru_small(B, L, n_in, n_h, layers, n_out, bias):
     (2, 512, 128, 256, 2, 128),      # the benchmark's sequence length and width
     (1, 1024, 128, 128, 1, 8),       # longest sequence the score tile holds
     (5, 1, 128, 128, 1, 8),          # one position per sequence: it attends to itself, z = 2h
+    (8, 100, 128, 256, 1, 8),        # a multiple of 8 sequences: whole sequences per XCD in the attention kernel
 ])
 def test_sru_with_sparsemax_attention(B, L, n_in, n_h, layers, n_out):
     """The attention variant of the predictor against the oracle: the attended states z element by
