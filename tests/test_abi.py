@@ -118,3 +118,15 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.sru_predict(p, C.byref(wa), 8, 2048, 1, p, None, p, 1 << 30, None) == UNS  # attention: L too long
     wa.attention = 3
     assert L.sru_predict(p, C.byref(wa), 8, 512, 1, p, None, p, 1 << 30, None) == INV
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU per box: the bench says so and exits before touching any device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr
+    assert r.stdout.strip() == ""
