@@ -2,12 +2,14 @@
 """Benchmark of the replicated top-1 MoE layer forward on one MI355X.
 
 A step = one pass of the whole layer path on one resident batch of synthetic tokens:
-moe_route -> replica_plan -> moe_dispatch -> moe_expert_ffn -> moe_combine (with --sru also
-sru_predict in front, its ids driving the plan).  Default workload: the Switch-base-128 shaped
-layer (T=4096, d=768, F=3072, E=128, capacity factor 1.25, replica budget 16, bf16 with fp32
-accumulation), Zipf(1.0)-skewed routing.  Prints ONE JSON line.
+moe_route -> moe_plan_dispatch (replica plan + dispatch tables) -> moe_expert_ffn (rows gathered
+through the permutation) -> moe_combine; the workloads with a predictor run sru_predict in front
+and its ids drive the plan.  Default workload: the Switch-base-128 shaped layer (T=4096, d=768,
+F=3072, E=128, capacity factor 1.25, replica budget 16, bf16 with fp32 accumulation),
+Zipf(1.0)-skewed routing.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3x|cfg4|cfg4b|cfg5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+                    [--workload cfg1|cfg2|cfg2k3|cfg3|cfg3x|cfg4|cfg4b|cfg5]
 """
 from __future__ import annotations
 
@@ -305,7 +307,9 @@ def main():
         cpu["value"] = round(cpu["value"], 1)
 
     line = {
-        "metric": "MoE-layer tokens/sec (route+dispatch+FFN+combine)", "value": modes["on"], "unit": "tokens/s",
+        # the matrix-core share of peak that the metric's name asks for is roofline.ffn_mfma_frac_of_bf16_peak
+        "metric": f"MoE-layer tokens/sec (route+dispatch+FFN+combine), MFMA %peak, E={E} d={d}",
+        "value": modes["on"], "unit": "tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_on, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if fp32 else "bf16", "data": "synthetic",
         "config": {"workload": desc, "name": a.workload, "T": T, "d_model": d, "d_ff": F, "experts": E,

@@ -1,7 +1,9 @@
-"""ctypes binding of ``libmoe_mpmc.so``: the same six calls (plus weight packing) on torch
-tensors.  Argument marshalling only -- every step of the path runs in the HIP kernels.  Torch
-is used for device memory and the current stream, nothing else.  There is no CPU fallback:
-if the library is missing or a call fails, an exception is raised.
+"""ctypes binding of ``libmoe_mpmc.so``: the library's calls under the same names (the six steps
+of the layer, weight packing, the fused plan + dispatch front end, the top-k variants) on torch
+tensors, and three small classes that hold preallocated buffers and issue the calls in order.
+Argument marshalling only -- every step of the path runs in the HIP kernels.  Torch is used for
+device memory and the current stream, nothing else.  There is no CPU fallback: if the library is
+missing or a call fails, an exception is raised.
 """
 from __future__ import annotations
 
@@ -100,7 +102,8 @@ def _dt(t: torch.Tensor) -> int:
 def _ptr(t):
     if t is None:
         return None
-    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    if not (t.is_cuda and t.is_contiguous()):
+        raise ValueError("device-resident contiguous tensors only")
     return C.c_void_p(t.data_ptr())
 
 
@@ -124,7 +127,8 @@ def moe_route(x, w_router, b_router=None, want_logits=False, out=None, ws=None, 
     E = w_router.shape[1]
     dev = x.device
     dt = _dt(x)
-    assert _dt(w_router) == dt and w_router.shape[0] == d
+    if _dt(w_router) != dt or w_router.shape[0] != d:
+        raise ValueError("w_router must be [d, E] (or its packed image) in the dtype of x")
     idx, prob = out if out is not None else (_i32(T, dev), torch.empty(T, dtype=torch.float32, device=dev))
     logits = torch.empty(T, E, dtype=torch.float32, device=dev) if want_logits else None
     need = lib().moe_route_workspace_bytes(T, d, E, dt)
@@ -291,7 +295,8 @@ def moe_route_topk(x, w_router, b_router, k, renormalize=False, want_logits=Fals
     E = w_router.shape[1]
     dev = x.device
     dt = _dt(x)
-    assert _dt(w_router) == dt and w_router.shape[0] == d
+    if _dt(w_router) != dt or w_router.shape[0] != d:
+        raise ValueError("w_router must be [d, E] (or its packed image) in the dtype of x")
     idx, wgt = out if out is not None else (_i32(k * T, dev).view(k, T),
                                             torch.empty(k, T, dtype=torch.float32, device=dev))
     logits = torch.empty(T, E, dtype=torch.float32, device=dev) if want_logits else None
@@ -370,11 +375,9 @@ class MoeLayerTopK:
         self.route_ws = _ws(L.moe_route_workspace_bytes(T, d, E, dt), dev)
         self.plan_out = dict(plan_counts=_i32(E, dev), replicas=_i32(E, dev), slot_base=_i32(E + 1, dev),
                              slot_expert=_i32(E + budget, dev), n_slots=_i32(1, dev))
-        self.plan_ws = _ws(L.replica_plan_workspace_bytes(A, E), dev)
         self.disp_out = dict(counts=_i32(E, dev), kept=_i32(E, dev), expert_offset=_i32(E + 1, dev),
                              slot_offset=_i32(self.max_slots + 1, dev), perm=_i32(A, dev),
                              inv=_i32(A, dev).view(k, T), row_token=_i32(A, dev), x_perm=None)
-        self.disp_ws = _ws(L.moe_dispatch_workspace_bytes(A, E), dev)
         self.front_ws = _ws(L.moe_plan_dispatch_workspace_bytes(A, T, k, E), dev)
         self.y_perm = torch.zeros(A, d, dtype=dtype, device=dev)
         self.ffn_ws = _ws(L.moe_expert_ffn_workspace_bytes(A, self.max_slots, d, F, dt), dev)

@@ -1,13 +1,12 @@
 // replica_plan: per-expert replica counts from (predicted) expert ids, within a slot budget.
 //
-// One workgroup of 1024 threads (for batches above 8192 ids the histogram is first built by
-// one workgroup per 8192 ids into the workspace and summed here).  All threads build the
-// histogram of ids in LDS (ids that
-// share a wavefront load are pre-counted with ballots, so a hot expert does not serialise the
-// LDS atomics).  Wavefront 0 then runs the integer allocation entirely in registers: lane l
-// owns experts l, l+64, ..., sums and arg-max searches are wavefront reductions, so the
-// one-by-one hand-out of the slots left by the floors needs no barrier.  All threads finally
-// scan the replica counts into slot_base and write the slot -> expert table.
+// One workgroup of 1024 threads (for batches above 8192 ids the histogram is first built by one
+// workgroup per 8192 ids into the workspace and summed here).  All threads build the histogram of
+// ids in LDS (ids that share a wavefront load are pre-counted with ballots, so a hot expert does
+// not serialise the LDS atomics).  Wavefront 0 then runs the integer allocation entirely in
+// registers: lane l owns experts l, l+64, ..., sums and arg-max searches are wavefront reductions,
+// so the one-by-one hand-out of the slots left by the floors needs no barrier.  All threads
+// finally scan the replica counts into slot_base and write the slot -> expert table.
 #include "plan_alloc.h"
 #include "route.h"
 
