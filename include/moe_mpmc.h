@@ -20,6 +20,10 @@
  *  - Return value: MOE_OK or a negative error code.  Arguments are validated on the host
  *    before anything is launched; on error nothing has been enqueued (MOE_ERR_HIP excepted).
  *    moe_last_error() returns a thread-local message for the last failing call.
+ *  - Empty batches (T = 0, B = 0, max_rows = 0) are valid: sizes and flags are still checked,
+ *    data pointers are not looked at and may be NULL; moe_route, sru_predict, moe_expert_ffn and
+ *    moe_combine then enqueue nothing, replica_plan, moe_dispatch and moe_plan_dispatch write
+ *    the tables of a batch without tokens (every expert one empty slot).
  *  - No C++ exception crosses the boundary.  Calls on different streams may overlap only if
  *    they use different workspaces and outputs.
  */

@@ -401,6 +401,7 @@ static int expert_ffn_checked(const void *x_perm, int n_x_rows, const int32_t *r
         MOE_REQUIRE(d % 64 == 0 && F % 64 == 0, MOE_ERR_UNSUPPORTED,
                     "moe_expert_ffn: fp32 path needs d and F multiples of 64 (d=%d F=%d)", d, F);
     }
+    if (max_rows == 0) return MOE_OK;   // an empty batch: nothing to read or write, pointers are not looked at
     MOE_REQUIRE(x_perm && w1 && w2 && slot_offset && slot_expert && n_slots && y_perm, MOE_ERR_INVALID_ARG,
                 "moe_expert_ffn: null pointer");
     MOE_REQUIRE(aligned16(x_perm) && aligned16(w1) && aligned16(w2) && aligned16(y_perm), MOE_ERR_INVALID_ARG,
@@ -408,7 +409,6 @@ static int expert_ffn_checked(const void *x_perm, int n_x_rows, const int32_t *r
     size_t need = moe_expert_ffn_workspace_bytes(max_rows, max_slots, d, F, dtype);
     MOE_REQUIRE(ws && aligned16(ws) && ws_bytes >= need, MOE_ERR_WORKSPACE,
                 "moe_expert_ffn: workspace of %zu bytes needed, %zu given", need, ws_bytes);
-    if (max_rows == 0) return MOE_OK;
 
     hipStream_t st = (hipStream_t)stream;
     size_t esz = dtype == MOE_F32 ? 4 : 2;

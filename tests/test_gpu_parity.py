@@ -456,3 +456,32 @@ def test_replication_invariance_no_drops():
     assert int(layer_c.plan_out["replicas"][hot].item()) == 3      # ceil(1500/700) slots
     assert int(layer_c.disp_out["expert_offset"][16].item()) == 1500
     assert torch.equal(a, out_c)
+
+
+# --------------------------------------------------------------------------- empty batch
+def test_empty_batch_through_every_call():
+    """T = 0: the index calls write the tables of a batch without tokens (checked against the
+    oracle), the tensor calls accept NULL data pointers and enqueue nothing."""
+    E, R, C, d, F = 8, 3, 5, 64, 128
+    none_i = torch.empty(0, dtype=torch.int32, device="cuda")
+    x = torch.empty(0, d, dtype=torch.float32, device="cuda")
+    w_r = to_dev(synth.normal_tensor((d, E), 0.02, [1], synth.F32))
+    idx, prob, _ = moe.moe_route(x, w_r)
+    assert idx.numel() == 0 and prob.numel() == 0
+    ref_pl = oracle.plan(np.zeros(0, np.int32), E, R, C)
+    pl = moe.replica_plan(none_i, E, R, C)
+    assert (to_host(pl["plan_counts"]) == ref_pl["counts"]).all()
+    for k in ("replicas", "slot_base", "slot_expert"):
+        assert (to_host(pl[k]) == ref_pl[k]).all(), k
+    assert int(pl["n_slots"].item()) == ref_pl["n_slots"]
+    ref_dp = oracle.dispatch(np.zeros((0, d), np.float32), np.zeros(0, np.int32), ref_pl["replicas"], E, C, E + R)
+    dp = moe.moe_dispatch(x, none_i, pl["replicas"], E, C, E + R)
+    for k in ("counts", "kept", "expert_offset", "slot_offset"):
+        assert (to_host(dp[k]) == ref_dp[k]).all(), k
+    w1 = to_dev(synth.normal_tensor((E, d, F), 0.02, [2], synth.F32))
+    w2 = to_dev(synth.normal_tensor((E, F, d), 0.02, [3], synth.F32))
+    y = moe.moe_expert_ffn(x, w1, w2, dp["slot_offset"], pl["slot_expert"], pl["n_slots"], E, F, max_slots=E + R)
+    assert y.shape == (0, d)
+    out = moe.moe_combine(y, x, none_i, prob, residual=1)
+    assert out.shape == (0, d)
+    _sync()
