@@ -246,20 +246,20 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
     }
 }
 
-// x_perm[pos] = x[perm[pos]] for pos < K.  32 lanes per row, 8 rows per workgroup, 16-byte
+// x_perm[pos] = x[perm[pos]] for pos < K (K is not read: the permutation ends in -1 entries).  32 lanes per row, 8 rows per workgroup, 16-byte
 // pieces: the scattered row reads and the contiguous writes are both whole lines, the row
 // index is read once per row, and all of a lane's loads are independent.
 constexpr int GATHER_ROWS = DSP_THREADS / 32;
 __global__ __launch_bounds__(DSP_THREADS) void dispatch_gather_kernel(const uint4 *__restrict__ x,
-                                                                      const int32_t *__restrict__ perm,
-                                                                      const int32_t *__restrict__ expert_offset, int E,
+                                                                      const int32_t *__restrict__ perm, int T,
                                                                       int n_tokens, int vec_per_row,
                                                                       uint4 *__restrict__ x_perm)
 {
     const int pos = blockIdx.x * GATHER_ROWS + (threadIdx.x >> 5);
     const int l = threadIdx.x & 31;
-    if (pos >= expert_offset[E]) return;
+    if (pos >= T) return;
     int row = perm[pos];
+    if (row < 0) return;                      // past the kept rows (perm holds -1 there): nothing to copy
     if (row >= n_tokens) row %= n_tokens;     // top-k: assignment -> its token
     const uint4 *src = x + (size_t)row * vec_per_row;
     uint4 *dst = x_perm + (size_t)pos * vec_per_row;
@@ -362,7 +362,7 @@ static int dispatch_checked(const char *who, const void *x, const int32_t *exper
             int vec_per_row = (int)((size_t)d * esz / 16);
             int grid = ceil_div(T, GATHER_ROWS);
             hipLaunchKernelGGL(dispatch_gather_kernel, dim3(grid), dim3(DSP_THREADS), 0, st, (const uint4 *)x, perm,
-                               expert_offset, E, n_tokens, vec_per_row, (uint4 *)x_perm);
+                               T, n_tokens, vec_per_row, (uint4 *)x_perm);
             MOE_CHECK_LAUNCH(who);
         }
     }

@@ -117,6 +117,7 @@ DISPATCH_CASES = [
     (5000, 72, 100, 9, 20, synth.BF16),
     (3001, 8, 1024, 2, 50, synth.BF16),
     (16384, 128, 256, 64, 32, synth.BF16),
+    (70001, 32, 300, 150, 64, synth.BF16),
 ]
 
 
