@@ -95,12 +95,13 @@ def _time_steps(step, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def _cpu_baseline(c, C, R, budget_s=20.0):
+def _cpu_baseline(c, C, R, budget_s=20.0, serial_leg=True):
     """The oracle as it stands, on the host cores: router, plan, dispatch and combine on the
     whole batch, the expert FFN on a sample of kept rows sized to ~budget_s, scaled to K."""
     import oracle
     T, E = c["T"], c["E"]
     k = c.get("top_k", 1)
+    oracle.route(c["x"][:64], c["w_router"], c["b_router"])      # untimed: loads the library, starts its threads
     t0 = time.perf_counter()
     if k == 1:
         rt = oracle.route(c["x"], c["w_router"], c["b_router"])
@@ -131,9 +132,19 @@ def _cpu_baseline(c, C, R, budget_s=20.0):
         oracle.combine_topk(y, c["x"], dp["inv"].reshape(k, T), rt["weight"], 0)
     t_back = time.perf_counter() - t0
     total = t_front + t_ffn + t_back
-    return dict(value=T / total, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
-                sample=f"router, plan, dispatch, combine on all {T} tokens; expert FFN on {n} of the {K} kept "
-                       f"rows, its time scaled by {K}/{n}")
+    res = dict(value=T / total, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+               sample=f"router, plan, dispatch, combine on all {T} tokens; expert FFN on {n} of the {K} kept "
+                      f"rows, its time scaled by {K}/{n}")
+    if serial_leg and total * res["cores"] < 30.0:
+        # the same work once more on one thread (small workloads only, where that stays within seconds)
+        cores = oracle.num_threads()
+        oracle.set_num_threads(1)
+        try:
+            one = _cpu_baseline(c, C, R, budget_s, serial_leg=False)
+        finally:
+            oracle.set_num_threads(cores)
+        res["value_1_thread"] = round(one["value"], 1)
+    return res
 
 
 def main():
@@ -231,6 +242,29 @@ def main():
     g1 = float(np.mean([t[0].elapsed_time(t[1]) for t in evs]))
     g2 = float(np.mean([t[1].elapsed_time(t[2]) for t in evs]))
 
+    # third pass: events between the calls of every step -> per-call times, and the spread over steps
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(a.steps)]
+
+    def step_marked(i):
+        m = marks[i]
+        m[5].record()                                  # step start (before the predictor, if any)
+        plan_ids = None
+        if sru is not None:
+            plan_ids, _ = moe.sru_predict(sru[0], sru[1], out=sru[2], ws=sru[3])
+        kw = {} if plan_ids is None else {"plan_ids": plan_ids}
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, marks=m[:5], **kw)
+
+    torch.cuda.synchronize()
+    for i in range(a.steps):
+        step_marked(i)
+    torch.cuda.synchronize()
+    call_names = ("sru_predict", "moe_route", "moe_plan_dispatch", "moe_expert_ffn", "moe_combine")
+    spans = ((5, 0), (0, 1), (1, 2), (2, 3), (3, 4))
+    per_call = {n: round(float(np.median([m[i].elapsed_time(m[j]) for m in marks])), 5)
+                for n, (i, j) in zip(call_names, spans) if n != "sru_predict" or sru is not None}
+    step_ms = [marks[i][5].elapsed_time(marks[i + 1][5]) for i in range(a.steps - 1)]
+    step_ms.append(marks[-1][5].elapsed_time(marks[-1][4]))
+
     kept = layer.disp_out["kept"].cpu().numpy()
     K = int(kept.sum())
     active = int((kept > 0).sum())
@@ -320,6 +354,9 @@ def main():
         "replication_modes_tokens_per_s": modes,
         "replication_modes_ms": extra_ms,
         "ms_per_step_with_kernel_events": round(ms_on_events, 5),
+        # from the pass with events between the calls (they cost a few us per step)
+        "ms_per_step_median_with_call_events": round(float(np.median(step_ms)), 5), "ms_per_step_min_with_call_events": round(float(np.min(step_ms)), 5),
+        "per_call_ms_median": per_call,
         "ms_per_step_hip_graph_replay": None if graph_ms is None else round(graph_ms, 5),
         "kept_tokens_budget0": kept0,
     }

@@ -34,13 +34,18 @@ def lib():
         build()
         _lib = C.CDLL(_LIB)
         for name in ("orc_route", "orc_sru", "orc_plan", "orc_dispatch", "orc_ffn",
-                     "orc_combine", "orc_num_threads"):
+                     "orc_combine", "orc_num_threads", "orc_set_num_threads"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
 
 def num_threads() -> int:
     return lib().orc_num_threads()
+
+
+def set_num_threads(n: int) -> int:
+    """Threads for the parallel loops from now on (timing only); returns the number in force."""
+    return lib().orc_set_num_threads(int(n))
 
 
 def _st(a: np.ndarray) -> int:

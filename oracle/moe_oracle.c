@@ -482,3 +482,13 @@ int orc_num_threads(void)
     return 1;
 #endif
 }
+
+/* Timing only (the serial leg of the CPU baseline): the number of threads the parallel loops use. */
+int orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    if (n >= 1) omp_set_num_threads(n);
+#endif
+    return orc_num_threads();
+}

@@ -384,15 +384,27 @@ class MoeLayerTopK:
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
 
     def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
-                out=None, router_layout=LAYOUT_PLAIN):
+                out=None, router_layout=LAYOUT_PLAIN, marks=None):
+        """marks: as in MoeLayer.forward."""
+        if marks is not None:
+            marks[0].record()
         idx, wgt, _ = moe_route_topk(x, w_router, b_router, self.k, self.renormalize, out=self.route_out,
                                      ws=self.route_ws, w_layout=router_layout)
+        if marks is not None:
+            marks[1].record()
         pl, dp = moe_plan_dispatch(idx.view(-1) if plan_ids is None else plan_ids, idx, self.E, self.R, self.C,
                                    self.policy, plan_out=self.plan_out, disp_out=self.disp_out, ws=self.front_ws)
+        if marks is not None:
+            marks[2].record()
         y = moe_expert_ffn_rows(x, dp["row_token"], self.k * self.T, w1, w2, dp["slot_offset"], pl["slot_expert"],
                                 pl["n_slots"], self.E, self.F, max_slots=self.max_slots, schedule=schedule,
                                 out=self.y_perm, ws=self.ffn_ws)
-        return moe_combine_topk(y, x, dp["inv"], wgt, residual, out=self.out if out is None else out)
+        if marks is not None:
+            marks[3].record()
+        o = moe_combine_topk(y, x, dp["inv"], wgt, residual, out=self.out if out is None else out)
+        if marks is not None:
+            marks[4].record()
+        return o
 
 
 # --------------------------------------------------------------------------- whole layer
@@ -422,11 +434,17 @@ class MoeLayer:
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
 
     def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
-                out=None, budget=None, router_layout=LAYOUT_PLAIN, fuse_gather=True, plan=None):
+                out=None, budget=None, router_layout=LAYOUT_PLAIN, fuse_gather=True, plan=None, marks=None):
         """plan: tables of a replica_plan call made earlier (e.g. by MoePipeline on another stream);
-        otherwise the plan is computed here from plan_ids, or from the router's own ids."""
+        otherwise the plan is computed here from plan_ids, or from the router's own ids.
+        marks: five torch.cuda.Event objects recorded before the router and after each of the four
+        calls (router, plan + dispatch, expert FFN, combine), for per-call timing."""
+        if marks is not None:
+            marks[0].record()
         idx, prob, _ = moe_route(x, w_router, b_router, out=self.route_out, ws=self.route_ws,
                                  w_layout=router_layout)
+        if marks is not None:
+            marks[1].record()
         R = self.R if budget is None else budget
         if R != self.R:
             raise ValueError("budget is fixed by the preallocated slot tables")
@@ -438,10 +456,17 @@ class MoeLayer:
                                                             self.C, self.policy, out=self.plan_out, ws=self.plan_ws)
             dp = moe_dispatch(None if fuse_gather else x, idx, pl["replicas"], self.E, self.C, self.max_slots,
                               out=self.disp_out, ws=self.disp_ws, shape=(self.T, self.d), dtype=x.dtype)
+        if marks is not None:
+            marks[2].record()
         y = moe_expert_ffn(x if fuse_gather else dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"],
                            pl["n_slots"], self.E, self.F, max_slots=self.max_slots, schedule=schedule,
                            out=self.y_perm, ws=self.ffn_ws, row_index=dp["perm"] if fuse_gather else None)
-        return moe_combine(y, x, dp["inv"], prob, residual, out=self.out if out is None else out)
+        if marks is not None:
+            marks[3].record()
+        o = moe_combine(y, x, dp["inv"], prob, residual, out=self.out if out is None else out)
+        if marks is not None:
+            marks[4].record()
+        return o
 
 
 class MoePipeline:
