@@ -1,18 +1,16 @@
 // sru_predict: SRU stack + linear head + argmax, the expert predictor.
 //
-// Per layer: (1) the concatenated weight [n_in, k*n_h] is re-laid into the packed image the
-// MFMA B operand wants (small, into the workspace); (2) one matrix-core product
-// U = X * [W | W_f | W_r | (W_h)] for all B*L tokens at once (the part of the SRU that is
-// parallel over time); (3) the recurrence.  The gates depend on the input only, so
-// c_t = f_t c_{t-1} + (1-f_t) x'_t is a linear recurrence in c: a workgroup takes 16 channels
-// of one sequence and cuts the time axis into 64 chunks; every thread first composes its
-// chunk into (A, B) with c_out = A c_in + B, the carries are chained through LDS, and each
-// thread then re-runs its chunk from its true carry-in and writes h_t (B * n_h * 64 threads,
-// enough to cover the chip at 8 sequences x 256 channels).  For sequences of up to 512 positions steps (2)
-// and (3) are one kernel per layer with the projections kept in LDS (sru_layer_fused_kernel below); the
-// two-kernel form serves longer sequences.  The head is a router-shaped product + argmax and reuses that
-// kernel.  Static weights may arrive already packed
-// (sru_weights.w_layout), which removes the per-call re-layout kernels.
+// Per layer: (1) the concatenated weight [n_in, k*n_h] is re-laid into the packed image the MFMA B
+// operand wants (small, into the workspace; skipped when the weights arrive packed, see
+// sru_weights.w_layout); (2) one matrix-core product U = X * [W | W_f | W_r | (W_h)] for all B*L
+// tokens at once (the part of the SRU that is parallel over time); (3) the recurrence.  The gates
+// depend on the input only, so c_t = f_t c_{t-1} + (1-f_t) x'_t is a linear recurrence in c: a
+// workgroup takes a few channels of one sequence and cuts the time axis into 64 chunks; every thread
+// first composes its chunk into (A, B) with c_out = A c_in + B, the 64 chunk maps of a channel are
+// composed by a scan, and each thread then re-runs its chunk from its true carry-in and writes h_t.
+// For sequences of up to 512 positions steps (2) and (3) are one kernel per layer with the projections
+// kept in LDS (sru_layer_fused_kernel below); the two-kernel form (sru_proj_kernel, sru_scan_kernel)
+// serves longer sequences.  The head is a router-shaped product + argmax and reuses the router's kernel.
 #include "gemm_bf16.h"
 #include "route.h"
 
