@@ -55,18 +55,20 @@ def _workload(name):
         c = synth.config_inputs(2)
         return c, c["C"], "Switch-base-128 layer T=4096 d=768 F=3072 E=128 CF=1.25 R=16 Zipf(1.0)"
     if name == "cfg3":
-        # the predictor runs in front of the workload-2 layer and its ids drive the replica plan
-        c = synth.config_inputs(2)
-        c["sru"] = synth.config_inputs(3)["sru"]
+        # The predictor runs in front of a workload-2 shaped layer and its ids drive the replica plan.  The
+        # layer's tokens and router are planted once the predictor's ids are known (main), so that the
+        # router agrees with the prediction on 85 % of the tokens and draws the rest from Zipf(1.0).
+        c = synth.config_inputs(3)
         return c, c["C"], ("2-layer SRU predictor (B=8 L=512 768->256, head 128) + Switch-base-128 layer "
-                           "T=4096 d=768 F=3072 E=128 CF=1.25 R=16")
+                           "T=4096 d=768 F=3072 E=128 CF=1.25 R=16, router agrees with the prediction on 85% of tokens")
     if name == "cfg3x":
         # the paper's predictor size: 10 SRU layers and the sparsemax attention in front of the head
-        c = synth.config_inputs(2)
+        c = synth.config_inputs(3)
         c["sru"] = synth.sru_inputs(8, 512, 768, 256, 10, 128, synth.BF16, synth.workloads.SEED0 + 33, w_std=0.05)
         c["sru"]["attention"] = True
         return c, c["C"], ("10-layer SRU predictor with sparsemax attention (B=8 L=512 768->256, head 128) + "
-                           "Switch-base-128 layer T=4096 d=768 F=3072 E=128 CF=1.25 R=16")
+                           "Switch-base-128 layer T=4096 d=768 F=3072 E=128 CF=1.25 R=16, router agrees with the "
+                           "prediction on 85% of tokens")
     if name == "cfg2k3":
         # top-3 routing on the workload-2 layer: 3 x 4096 assignments, slot capacity scaled by k
         c = synth.config_inputs(2)
@@ -173,6 +175,28 @@ def main():
 
     c, C, desc = _workload(a.workload)
     T, d, F, E, R = c["T"], c["d"], c["F"], c["E"], c["R"]
+    sru = None
+    if "sru" in c:
+        import synth
+        s_ = c["sru"]
+        sru_w = moe.SruWeights([_to_dev(w) for w in s_["w_cat"]], None, None, _to_dev(s_["w_head"]), None, pack=True,
+                               attention=bool(s_.get("attention", False)))
+        emb = _to_dev(s_["emb"])
+        pred = torch.empty(T, dtype=torch.int32, device="cuda")
+        sru_ws = torch.empty(moe.lib().sru_predict_workspace_bytes(__import__("ctypes").byref(sru_w.c), s_["B"],
+                                                                   s_["L"], moe.MOE_BF16), dtype=torch.uint8,
+                             device="cuda")
+        sru = (emb, sru_w, pred, sru_ws)
+        if "x" not in c:
+            # the layer of this workload: ids that agree with the predictor's on `agree` of the tokens, planted
+            # as the largest router logit of their token (pure input generation; no method arithmetic)
+            moe.sru_predict(emb, sru_w, out=pred, ws=sru_ws)
+            torch.cuda.synchronize()
+            seed = synth.workloads.SEED0 + 3
+            z = synth.mix_ids(pred.cpu().numpy(), E, c["agree"], c["zipf_s"], seed)
+            lay = synth.planted_layer_inputs(z, d, F, E, c["dtype"], seed, c["alpha"], c["beta"], 1)
+            c.update({k: v for k, v in lay.items() if k != "layers"})
+            c.update(lay["layers"][0])
     fp32 = c["x"].dtype == np.float32
     dt = torch.float32 if fp32 else torch.bfloat16
     x, b = _to_dev(c["x"]), _to_dev(c["b_router"])
@@ -194,17 +218,6 @@ def main():
     else:
         layer = moe.MoeLayerTopK(T, d, F, E, top_k, R, C, dt)
         layer0 = moe.MoeLayerTopK(T, d, F, E, top_k, 0, C, dt)
-    sru = None
-    if "sru" in c:
-        s_ = c["sru"]
-        sru_w = moe.SruWeights([_to_dev(w) for w in s_["w_cat"]], None, None, _to_dev(s_["w_head"]), None, pack=True,
-                               attention=bool(s_.get("attention", False)))
-        emb = _to_dev(s_["emb"])
-        pred = torch.empty(T, dtype=torch.int32, device="cuda")
-        sru_ws = torch.empty(moe.lib().sru_predict_workspace_bytes(__import__("ctypes").byref(sru_w.c), s_["B"],
-                                                                   s_["L"], moe.MOE_BF16), dtype=torch.uint8,
-                             device="cuda")
-        sru = (emb, sru_w, pred, sru_ws)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(a.steps)]
     for trio in evs:
         for e in trio:
@@ -224,11 +237,17 @@ def main():
             layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL,
                           plan_ids=plan_ids)
 
+    def _plan_kw():
+        # with a predictor in front, every mode runs it and plans from its ids
+        if sru is None:
+            return {}
+        return {"plan_ids": moe.sru_predict(sru[0], sru[1], out=sru[2], ws=sru[3])[0]}
+
     def step_off_same_plan():
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=RL)
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=RL, **_plan_kw())
 
     def step_off_budget0():
-        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL)
+        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, **_plan_kw())
 
     for _ in range(a.warmup):
         step_on()
@@ -266,6 +285,15 @@ def main():
     step_ms.append(marks[-1][5].elapsed_time(marks[-1][4]))
 
     kept = layer.disp_out["kept"].cpu().numpy()
+    counts = layer.disp_out["counts"].cpu().numpy().astype(np.int64)
+    replicas = layer.plan_out["replicas"].cpu().numpy()
+    # the realised skew of this batch (a description of the input, taken from the library's own tables)
+    routing = {"assignments": int(counts.sum()), "max_expert_share": round(float(counts.max() / max(1, counts.sum())), 4),
+               "experts_over_slot_capacity": int((counts > C).sum()),
+               "replicas_wanted": int(np.maximum(0, -(-counts // C) - 1).sum()),
+               "replicas_granted": int(replicas.sum() - E)}
+    if sru is not None:
+        routing["router_agrees_with_prediction"] = round(float((layer.route_out[0] == sru[2]).float().mean().item()), 4)
     K = int(kept.sum())
     active = int((kept > 0).sum())
     n_slots = int(layer.plan_out["n_slots"].item())
@@ -336,9 +364,11 @@ def main():
         del src, dst
 
     cpu = None
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and sru is None:
         cpu = _cpu_baseline(c, C, R)
         cpu["value"] = round(cpu["value"], 1)
+    # (with a predictor in front, the layer's inputs were planted from the library's own predictions, and the
+    # oracle is never fed anything that came out of the HIP path: its baseline is the one of workload cfg2)
 
     line = {
         # the matrix-core share of peak that the metric's name asks for is roofline.ffn_mfma_frac_of_bf16_peak
@@ -348,7 +378,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if fp32 else "bf16", "data": "synthetic",
         "config": {"workload": desc, "name": a.workload, "T": T, "d_model": d, "d_ff": F, "experts": E,
                    "top_k": top_k, "slot_capacity": C, "replica_budget": R, "kept_tokens": K, "active_experts": active,
-                   "slots": n_slots, "replication": "on (slot schedule)"},
+                   "slots": n_slots, "replication": "on (slot schedule)", "routing": routing},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "replication_modes_tokens_per_s": modes,
