@@ -175,6 +175,8 @@ def sru_predict(emb, weights: SruWeights, want_logits=False, out=None, ws=None):
     if ws is None:
         need = lib().sru_predict_workspace_bytes(C.byref(weights.c), B, L, dt)
         if need == 0:
+            # the size query answers 0 for arguments the library rejects: make the call itself, with no
+            # tensors, so that its validation names what is wrong
             _check(lib().sru_predict(None, C.byref(weights.c), B, L, dt, None, None, None, 0, None) or -2)
         ws = _ws(need, dev)
     _check(lib().sru_predict(_ptr(emb), C.byref(weights.c), B, L, dt, _ptr(pred), _ptr(logits), _ptr(ws),
@@ -434,7 +436,7 @@ class MoeLayer:
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
 
     def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
-                out=None, budget=None, router_layout=LAYOUT_PLAIN, fuse_gather=True, plan=None, marks=None):
+                out=None, router_layout=LAYOUT_PLAIN, fuse_gather=True, plan=None, marks=None):
         """plan: tables of a replica_plan call made earlier (e.g. by MoePipeline on another stream);
         otherwise the plan is computed here from plan_ids, or from the router's own ids.
         marks: five torch.cuda.Event objects recorded before the router and after each of the four
@@ -445,9 +447,7 @@ class MoeLayer:
                                  w_layout=router_layout)
         if marks is not None:
             marks[1].record()
-        R = self.R if budget is None else budget
-        if R != self.R:
-            raise ValueError("budget is fixed by the preallocated slot tables")
+        R = self.R
         if plan is None and fuse_gather:
             pl, dp = moe_plan_dispatch(idx if plan_ids is None else plan_ids, idx, self.E, R, self.C, self.policy,
                                        plan_out=self.plan_out, disp_out=self.disp_out, ws=self.front_ws)
