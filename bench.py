@@ -30,9 +30,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch (fetched + written) of the two FFN GEMM kernels, from two rocprofv3 --pmc
 # runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads
 # for a plain 1 GiB copy (fetch x1.9999, write x1.0000); figures and commands in
-# profiles/moe_layer_cfg2.md.  Counters cannot be read inside a normal run, so the value is
+# profiles/moe_layer_cfg2.md (and _cfg4, _cfg5).  Counters cannot be read inside a normal run, so the value is
 # carried here and refreshed whenever those kernels change.
 PMC_TRAFFIC_BYTES = {"cfg2": {"ffn_gemm1": 631.31e6 + 15.12e6, "ffn_gemm2": 621.04e6 + 3.78e6},
+                     "cfg4": {"ffn_gemm1": 1252.55e6 + 40.63e6, "ffn_gemm2": 1231.44e6 + 10.16e6},
                      # cfg5: every row goes through the 256 x 256 tile kernel
                      "cfg5": {"ffn_gemm1": 2075.61e6 + 402.65e6, "ffn_gemm2": 2237.68e6 + 100.66e6}}
 
