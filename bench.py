@@ -35,7 +35,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 PMC_TRAFFIC_BYTES = {"cfg2": {"ffn_gemm1": 631.31e6 + 15.12e6, "ffn_gemm2": 621.04e6 + 3.78e6},
                      "cfg4": {"ffn_gemm1": 1252.55e6 + 40.63e6, "ffn_gemm2": 1231.44e6 + 10.16e6},
                      # cfg5: every row goes through the 256 x 256 tile kernel
-                     "cfg5": {"ffn_gemm1": 2075.61e6 + 402.65e6, "ffn_gemm2": 2237.68e6 + 100.66e6}}
+                     "cfg5": {"ffn_gemm1": 2060.13e6 + 402.65e6, "ffn_gemm2": 2236.10e6 + 100.66e6}}
 
 
 def _to_dev(a):
@@ -84,7 +84,9 @@ def _workload(name):
     if name == "cfg5":
         c = synth.config_inputs(5)
         c.update(c["layers"][0])
-        return c, c["C"], "extreme skew, one layer of the stack: T=65536 E=256 CF=4.0 R=64, 50% hot expert"
+        c["residual"] = 1
+        return c, c["C"], ("extreme skew, one layer of the stack (with its residual connection): T=65536 E=256 "
+                           "CF=4.0 R=64, 50% hot expert")
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -130,9 +132,9 @@ def _cpu_baseline(c, C, R, budget_s=20.0, serial_leg=True):
     t_ffn = (time.perf_counter() - t0) * (K / n)
     t0 = time.perf_counter()
     if k == 1:
-        oracle.combine(y, c["x"], dp["inv"], rt["prob"], 0)
+        oracle.combine(y, c["x"], dp["inv"], rt["prob"], int(c.get("residual", 0)))
     else:
-        oracle.combine_topk(y, c["x"], dp["inv"].reshape(k, T), rt["weight"], 0)
+        oracle.combine_topk(y, c["x"], dp["inv"].reshape(k, T), rt["weight"], int(c.get("residual", 0)))
     t_back = time.perf_counter() - t0
     total = t_front + t_ffn + t_back
     res = dict(value=T / total, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
@@ -213,6 +215,7 @@ def main():
     torch.cuda.synchronize()
 
     top_k = c.get("top_k", 1)
+    RES = int(c.get("residual", 0))      # the layers of the workload-5 stack add their input (residual connection)
     if top_k == 1:
         layer = moe.MoeLayer(T, d, F, E, R, C, dt)
         layer0 = moe.MoeLayer(T, d, F, E, 0, C, dt)          # budget 0: the plain Switch layer
@@ -233,9 +236,9 @@ def main():
             moe.set_ffn_timing_events(*evs[it["i"]])
             it["i"] += 1
         if plan_ids is None:
-            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL)
+            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, residual=RES)
         else:
-            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL,
+            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, residual=RES,
                           plan_ids=plan_ids)
 
     def _plan_kw():
@@ -245,10 +248,10 @@ def main():
         return {"plan_ids": moe.sru_predict(sru[0], sru[1], out=sru[2], ws=sru[3])[0]}
 
     def step_off_same_plan():
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=RL, **_plan_kw())
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=RL, residual=RES, **_plan_kw())
 
     def step_off_budget0():
-        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, **_plan_kw())
+        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, residual=RES, **_plan_kw())
 
     for _ in range(a.warmup):
         step_on()
@@ -272,7 +275,7 @@ def main():
         if sru is not None:
             plan_ids, _ = moe.sru_predict(sru[0], sru[1], out=sru[2], ws=sru[3])
         kw = {} if plan_ids is None else {"plan_ids": plan_ids}
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, marks=m[:5], **kw)
+        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, residual=RES, marks=m[:5], **kw)
 
     torch.cuda.synchronize()
     for i in range(a.steps):
@@ -337,7 +340,7 @@ def main():
 
         def step_pipelined():
             pipe.predict(sru[0])
-            pipe.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL)
+            pipe.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, residual=RES)
 
         for _ in range(a.warmup):
             step_pipelined()
@@ -379,7 +382,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if fp32 else "bf16", "data": "synthetic",
         "config": {"workload": desc, "name": a.workload, "T": T, "d_model": d, "d_ff": F, "experts": E,
                    "top_k": top_k, "slot_capacity": C, "replica_budget": R, "kept_tokens": K, "active_experts": active,
-                   "slots": n_slots, "replication": "on (slot schedule)", "routing": routing},
+                   "slots": n_slots, "replication": "on (slot schedule)", "residual": RES, "routing": routing},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "replication_modes_tokens_per_s": modes,
