@@ -9,7 +9,7 @@ F=3072, E=128, capacity factor 1.25, replica budget 16, bf16 with fp32 accumulat
 Zipf(1.0)-skewed routing.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
-                    [--workload cfg1|cfg2|cfg2k3|cfg3|cfg3x|cfg4|cfg4b|cfg5]
+                    [--workload cfg1|cfg2|cfg2k3|cfg3|cfg3x|cfg4|cfg4b|cfg5|cfg5stack]
 """
 from __future__ import annotations
 
@@ -87,6 +87,12 @@ def _workload(name):
         c["residual"] = 1
         return c, c["C"], ("extreme skew, one layer of the stack (with its residual connection): T=65536 E=256 "
                            "CF=4.0 R=64, 50% hot expert")
+    if name == "cfg5stack":
+        c = synth.config_inputs(5)
+        c["residual"] = 1
+        c["stack"] = True
+        return c, c["C"], (f"extreme skew, the whole stack: {len(c['layers'])} MoE layers per step with independent "
+                           "weights and a residual connection between them, T=65536 E=256 CF=4.0 R=64, 50% hot expert")
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -202,17 +208,29 @@ def main():
             c.update(lay["layers"][0])
     fp32 = c["x"].dtype == np.float32
     dt = torch.float32 if fp32 else torch.bfloat16
-    x, b = _to_dev(c["x"]), _to_dev(c["b_router"])
-    if fp32:
-        wr, w1, w2 = _to_dev(c["w_router"]), _to_dev(c["w1"]), _to_dev(c["w2"])
-        RL = moe.LAYOUT_PLAIN
-    else:
-        # static weights are packed once, outside the timed region (router included)
-        wr = moe.moe_pack_weights(_to_dev(c["w_router"])[None].contiguous())[0]
-        w1 = moe.moe_pack_weights(_to_dev(c["w1"]))
-        w2 = moe.moe_pack_weights(_to_dev(c["w2"]))
-        RL = moe.LAYOUT_PACKED
-    torch.cuda.synchronize()
+    x = _to_dev(c["x"])
+    RL = moe.LAYOUT_PLAIN if fp32 else moe.LAYOUT_PACKED
+    layer_inputs = c["layers"] if c.get("stack") else [c]
+    W = []                                   # per layer: router matrix, router bias, W1, W2 on the device
+    for lw in layer_inputs:
+        if fp32:
+            W.append((_to_dev(lw["w_router"]), _to_dev(lw["b_router"]), _to_dev(lw["w1"]), _to_dev(lw["w2"])))
+        else:
+            # static weights are packed once, outside the timed region (router included)
+            W.append((moe.moe_pack_weights(_to_dev(lw["w_router"])[None].contiguous())[0], _to_dev(lw["b_router"]),
+                      moe.moe_pack_weights(_to_dev(lw["w1"])), moe.moe_pack_weights(_to_dev(lw["w2"]))))
+        torch.cuda.synchronize()
+    n_layers = len(W)
+    wr, b, w1, w2 = W[0]
+    # a stack hands the output of one layer to the next: two buffers in turn
+    outs = [torch.empty(T, d, dtype=dt, device="cuda") for _ in range(2)] if n_layers > 1 else None
+
+    def chain(lay, schedule, marks=None, **kw):
+        cur = x
+        for l, (wr_l, b_l, w1_l, w2_l) in enumerate(W):
+            cur = lay.forward(cur, wr_l, b_l, w1_l, w2_l, schedule=schedule, router_layout=RL, residual=RES,
+                              out=None if outs is None else outs[l % 2], marks=marks if l == 0 else None, **kw)
+        return cur
 
     top_k = c.get("top_k", 1)
     RES = int(c.get("residual", 0))      # the layers of the workload-5 stack add their input (residual connection)
@@ -236,10 +254,9 @@ def main():
             moe.set_ffn_timing_events(*evs[it["i"]])
             it["i"] += 1
         if plan_ids is None:
-            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, residual=RES)
+            chain(layer, moe.SCHEDULE_SLOTS)
         else:
-            layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, residual=RES,
-                          plan_ids=plan_ids)
+            chain(layer, moe.SCHEDULE_SLOTS, plan_ids=plan_ids)
 
     def _plan_kw():
         # with a predictor in front, every mode runs it and plans from its ids
@@ -248,10 +265,10 @@ def main():
         return {"plan_ids": moe.sru_predict(sru[0], sru[1], out=sru[2], ws=sru[3])[0]}
 
     def step_off_same_plan():
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=RL, residual=RES, **_plan_kw())
+        chain(layer, moe.SCHEDULE_EXPERTS, **_plan_kw())
 
     def step_off_budget0():
-        layer0.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, residual=RES, **_plan_kw())
+        chain(layer0, moe.SCHEDULE_SLOTS, **_plan_kw())
 
     for _ in range(a.warmup):
         step_on()
@@ -275,18 +292,20 @@ def main():
         if sru is not None:
             plan_ids, _ = moe.sru_predict(sru[0], sru[1], out=sru[2], ws=sru[3])
         kw = {} if plan_ids is None else {"plan_ids": plan_ids}
-        layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_SLOTS, router_layout=RL, residual=RES, marks=m[:5], **kw)
+        chain(layer, moe.SCHEDULE_SLOTS, marks=m[:5], **kw)       # the marks sit in the first layer of a stack
 
+    end_ev = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     for i in range(a.steps):
         step_marked(i)
+    end_ev.record()
     torch.cuda.synchronize()
     call_names = ("sru_predict", "moe_route", "moe_plan_dispatch", "moe_expert_ffn", "moe_combine")
     spans = ((5, 0), (0, 1), (1, 2), (2, 3), (3, 4))
     per_call = {n: round(float(np.median([m[i].elapsed_time(m[j]) for m in marks])), 5)
                 for n, (i, j) in zip(call_names, spans) if n != "sru_predict" or sru is not None}
     step_ms = [marks[i][5].elapsed_time(marks[i + 1][5]) for i in range(a.steps - 1)]
-    step_ms.append(marks[-1][5].elapsed_time(marks[-1][4]))
+    step_ms.append(marks[-1][5].elapsed_time(end_ev))
 
     kept = layer.disp_out["kept"].cpu().numpy()
     counts = layer.disp_out["counts"].cpu().numpy().astype(np.int64)
@@ -382,7 +401,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if fp32 else "bf16", "data": "synthetic",
         "config": {"workload": desc, "name": a.workload, "T": T, "d_model": d, "d_ff": F, "experts": E,
                    "top_k": top_k, "slot_capacity": C, "replica_budget": R, "kept_tokens": K, "active_experts": active,
-                   "slots": n_slots, "replication": "on (slot schedule)", "residual": RES, "routing": routing},
+                   "slots": n_slots, "replication": "on (slot schedule)", "residual": RES, "layers_per_step": n_layers,
+                   "routing": routing},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "replication_modes_tokens_per_s": modes,
