@@ -20,15 +20,6 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + \
-        glob.glob(os.path.join(HERE, "..", "include", "*.h"))
-    return any(os.path.getmtime(p) > t for p in deps)
-
-
 def build_library(verbose: bool = False) -> str:
     """One hipcc -c per source, side by side, then one link."""
     from concurrent.futures import ThreadPoolExecutor
