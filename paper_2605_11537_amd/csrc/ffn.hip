@@ -268,23 +268,30 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restri
     for (int r0 = it.row_begin; r0 < row_end; r0 += FFN_BM) {
         const int nrows = row_end - r0 < FFN_BM ? row_end - r0 : FFN_BM;
         float acc[4][4] = {};
+        // this thread's pieces of a 16-deep chunk: 4 consecutive k of token row r, 4 consecutive columns of
+        // weight row kb.  The next chunk is fetched into registers while the current one is multiplied, so a
+        // chunk costs its arithmetic and not a memory round trip.
+        const int r = threadIdx.x >> 2, kq = (threadIdx.x & 3) * 4;
+        const int kb = threadIdx.x >> 4, nb = (threadIdx.x & 15) * 4;
+        const float *a_src = nullptr;
+        if (r < nrows) {
+            const int src = row_index ? row_index[r0 + r] : r0 + r;
+            if (src >= 0 && src < n_src_rows) a_src = A + (size_t)src * K + kq;
+        }
+        auto fetch = [&](int k0, float4 &av, float4 &bv) {
+            av = a_src ? *reinterpret_cast<const float4 *>(a_src + k0) : make_float4(0.f, 0.f, 0.f, 0.f);
+            bv = *reinterpret_cast<const float4 *>(B + (size_t)(k0 + kb) * N + nb);
+        };
+        float4 av, bv;
+        fetch(0, av, bv);
         for (int k0 = 0; k0 < K; k0 += 16) {
-            {   // A chunk 64 rows x 16 k: thread loads 4 consecutive k of one row
-                int r = threadIdx.x >> 2, kq = (threadIdx.x & 3) * 4;
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (r < nrows) {
-                    int src = row_index ? row_index[r0 + r] : r0 + r;
-                    if (src >= 0 && src < n_src_rows) v = *reinterpret_cast<const float4 *>(A + (size_t)src * K + k0 + kq);
-                }
-                As[kq + 0][r] = v.x;
-                As[kq + 1][r] = v.y;
-                As[kq + 2][r] = v.z;
-                As[kq + 3][r] = v.w;
-                int kb = threadIdx.x >> 4, nb = (threadIdx.x & 15) * 4;
-                *reinterpret_cast<float4 *>(&Bs[kb][nb]) =
-                    *reinterpret_cast<const float4 *>(B + (size_t)(k0 + kb) * N + nb);
-            }
+            As[kq + 0][r] = av.x;
+            As[kq + 1][r] = av.y;
+            As[kq + 2][r] = av.z;
+            As[kq + 3][r] = av.w;
+            *reinterpret_cast<float4 *>(&Bs[kb][nb]) = bv;
             __syncthreads();
+            if (k0 + 16 < K) fetch(k0 + 16, av, bv);
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
                 float a[4], b[4];
@@ -301,14 +308,14 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float *__restri
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            int r = ty * 4 + i;
-            if (r < nrows) {
+            const int orow = ty * 4 + i;
+            if (orow < nrows) {
                 float4 o;
                 o.x = RELU ? fmaxf(acc[i][0], 0.f) : acc[i][0];
                 o.y = RELU ? fmaxf(acc[i][1], 0.f) : acc[i][1];
                 o.z = RELU ? fmaxf(acc[i][2], 0.f) : acc[i][2];
                 o.w = RELU ? fmaxf(acc[i][3], 0.f) : acc[i][3];
-                *reinterpret_cast<float4 *>(C + (size_t)(r0 + r) * N + nt * 64 + tx * 4) = o;
+                *reinterpret_cast<float4 *>(C + (size_t)(r0 + orow) * N + nt * 64 + tx * 4) = o;
             }
         }
     }
