@@ -228,8 +228,10 @@ def main():
     def chain(lay, schedule, marks=None, **kw):
         cur = x
         for l, (wr_l, b_l, w1_l, w2_l) in enumerate(W):
+            ffn_events = kw.pop("ffn_events", None) if l == 0 else None     # first layer of a stack only
             cur = lay.forward(cur, wr_l, b_l, w1_l, w2_l, schedule=schedule, router_layout=RL, residual=RES,
-                              out=None if outs is None else outs[l % 2], marks=marks if l == 0 else None, **kw)
+                              out=None if outs is None else outs[l % 2], marks=marks if l == 0 else None,
+                              ffn_events=ffn_events, **kw)
         return cur
 
     top_k = c.get("top_k", 1)
@@ -250,13 +252,11 @@ def main():
         plan_ids = None
         if sru is not None:
             plan_ids, _ = moe.sru_predict(sru[0], sru[1], out=sru[2], ws=sru[3])
+        kw = {} if plan_ids is None else {"plan_ids": plan_ids}
         if it["timed"]:
-            moe.set_ffn_timing_events(*evs[it["i"]])
+            kw["ffn_events"] = evs[it["i"]]
             it["i"] += 1
-        if plan_ids is None:
-            chain(layer, moe.SCHEDULE_SLOTS)
-        else:
-            chain(layer, moe.SCHEDULE_SLOTS, plan_ids=plan_ids)
+        chain(layer, moe.SCHEDULE_SLOTS, **kw)
 
     def _plan_kw():
         # with a predictor in front, every mode runs it and plans from its ids

@@ -58,10 +58,13 @@ extern "C" {
 
 const char *moe_last_error(void);
 int moe_version(void);
+/* Identifier of the sources this binary was compiled from (a hash the build step passes in; "unknown"
+ * for a build made some other way).  The Python binding compares it with the sources beside it. */
+const char *moe_build_id(void);
 
 /* ---------------------------------------------------------------------------------------
- * moe_route -- the softmax gate of the top-1 layer (Methodology: "a model similar to
- * SwitchTransformers (top-1)"; Preliminaries: routing via softmax).
+ * moe_route -- the softmax gate of the top-1 layer (Methodology: the model run is a
+ * Switch-Transformer-like top-1 layer; Preliminaries: routing via softmax).
  *   logit[s][e] = sum_k x[s][k] * w_router[k][e] + b_router[e]
  *   expert_idx[s]  = argmax_e logit[s][e]          (lowest e on an exact tie)
  *   expert_prob[s] = softmax(logit[s])[expert_idx[s]]
@@ -117,7 +120,7 @@ int moe_combine_topk(const void *y_perm, const void *x, const int32_t *inv, cons
                      int T, int k, int d, int dtype, int residual, void *out, void *stream);
 
 /* ---------------------------------------------------------------------------------------
- * sru_predict -- the expert predictor h_l of Algorithm 2 ("Expert k <- h_l(X_i[s])"): a stack
+ * sru_predict -- the expert predictor h_l of Algorithm 2 (the step that assigns a token its expert): a stack
  * of SRU layers (equations of the subsection "Simple Recurrent Unit (SRU) for expert
  * prediction") followed by a linear head and an argmax.
  *   per layer and sequence, t = 0..L-1, c_{-1} = 0:
@@ -144,8 +147,8 @@ typedef struct sru_weights {
     const void *w_head;
     const float *b_head;
     int attention; /* 0: the head reads the last layer's states h_t.  1: sparsemax self-attention first
-                      ("SRU-based predictor with sparse attention", Methodology; SRU subsection, last
-                      paragraph -- the paper prints no equations, this is the reading built): inside
+                      (the predictor's sparse attention: Methodology; SRU subsection, last paragraph --
+                      the paper prints no equations, this is the reading built): inside
                       each sequence s[t,j] = <h_t,h_j>/sqrt(n_hidden), a[t,:] = sparsemax(s[t,:]) (the
                       Euclidean projection onto the simplex: exact zeros for less relevant positions),
                       z_t = h_t + sum_j a[t,j] h_j rounded to dtype, and the head reads z_t.
@@ -247,6 +250,9 @@ int moe_pack_weights(const void *w, int E, int K, int N, int dtype, void *w_pack
  * then never written to HBM.  x_perm must hold max_rows rows; an index outside [0, max_rows)
  * is never dereferenced (the row is computed from a zero row or from row 0, its output is
  * unspecified).  y_perm stays in permuted row order either way.
+ * Workspace layout: h occupies the first max_rows*F elements (row-major [max_rows, F], dtype) and
+ * still holds the first product's output when the call's kernels have finished (rows outside all
+ * slots are not written); the work lists follow it.
  */
 size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, int d, int F, int dtype);
 int moe_expert_ffn(const void *x_perm, const int32_t *row_index, const void *w1, const void *w2,
@@ -254,12 +260,6 @@ int moe_expert_ffn(const void *x_perm, const int32_t *row_index, const void *w1,
                    const int32_t *slot_offset, const int32_t *slot_expert, const int32_t *n_slots,
                    int max_rows, int max_slots, int E, int d, int F, int dtype, int schedule,
                    void *y_perm, void *ws, size_t ws_bytes, void *stream);
-
-/* Measurement hook (not part of the method): the next moe_expert_ffn call made by this host
- * thread records the three hipEvent_t handles (passed as void*, any may be NULL) on its
- * stream: before its first GEMM kernel, between the two GEMM kernels, after the second.  The
- * handles are forgotten after that call. */
-int moe_expert_ffn_set_timing_events(void *before_gemm1, void *between, void *after_gemm2);
 
 /* ---------------------------------------------------------------------------------------
  * moe_combine -- expert output scaled by the gate probability, back in token order; tokens
@@ -272,6 +272,19 @@ int moe_expert_ffn_set_timing_events(void *before_gemm1, void *between, void *af
  */
 int moe_combine(const void *y_perm, const void *x, const int32_t *inv, const float *expert_prob,
                 int T, int d, int dtype, int residual, void *out, void *stream);
+
+/* =======================================================================================
+ * Measurement (not part of the method; used by the benchmark only).
+ * moe_expert_ffn_timed: moe_expert_ffn_rows (with row_index NULL: moe_expert_ffn, n_x_rows =
+ * max_rows) that also records three hipEvent_t handles (passed as void*, any may be NULL) on the
+ * call's stream: before its first product's kernel, between the two products, after the second.
+ * It keeps no state: the events belong to this one call.  Same outputs as the untimed calls.
+ */
+int moe_expert_ffn_timed(const void *x, int n_x_rows, const int32_t *row_index, const void *w1,
+                         const void *w2, int weight_layout, const int32_t *slot_offset,
+                         const int32_t *slot_expert, const int32_t *n_slots, int max_rows, int max_slots,
+                         int E, int d, int F, int dtype, int schedule, void *y_perm, void *ws,
+                         size_t ws_bytes, void *stream, void *ev_before, void *ev_between, void *ev_after);
 
 #ifdef __cplusplus
 }

@@ -2,8 +2,7 @@
  * CPU oracle for the replicated top-1 MoE layer forward.  TEST INFRASTRUCTURE ONLY.
  *
  * A plain, slow, obviously-correct evaluation of what the hot path computes, written from the
- * paper: the Switch-style top-1 layer the paper's Methodology section runs ("a model similar
- * to SwitchTransformers (top-1)"), the replication pass of Algorithm 1, the capping heuristic
+ * paper: the Switch-style top-1 layer the paper's Methodology section runs, the replication pass of Algorithm 1, the capping heuristic
  * of the "Capacity capping" subsection, and the SRU equations of the "Simple Recurrent Unit
  * for expert prediction" subsection.  It shares no code with the GPU library and must never
  * be called from the product path: only the tests, the smoke check and the bench's CPU
@@ -211,8 +210,8 @@ int orc_sru(const void *emb, int B, int L, int n_layers, int n_in, int n_h, int 
  *   want_e = extra physical slots expert e would get from Algorithm 1 if every slot holds at
  *            most C tokens: ceil(n_e / C) - 1 (C = 1 is the algorithm as printed: one
  *            replica per further token).
- *   Every expert owns one slot ("each distinct expert gets a count of at least 1"; all
- *   experts stay resident here).  If the wanted extras D = sum want_e fit in the budget R
+ *   Every expert owns one slot (Capacity capping subsection: no distinct expert's count falls
+ *   below one; all experts stay resident here).  If the wanted extras D = sum want_e fit in the budget R
  *   they are all granted.  Otherwise the remaining space is divided by the count of replicas
  *   still to be added and the limits raised accordingly:
  *     policy 0: extra_e = floor(R * want_e / D); the < |wanting| slots that the floors leave

@@ -21,13 +21,13 @@ LIB_PATH = os.path.join(_HERE, "libmoe_mpmc.so")
 _lib = None
 
 EXPORTS = (
-    "moe_last_error", "moe_version",
+    "moe_last_error", "moe_version", "moe_build_id",
     "moe_route_workspace_bytes", "moe_route",
     "sru_predict_workspace_bytes", "sru_predict",
     "replica_plan_workspace_bytes", "replica_plan",
     "moe_dispatch_workspace_bytes", "moe_dispatch",
     "moe_packed_weights_bytes", "moe_pack_weights",
-    "moe_expert_ffn_workspace_bytes", "moe_expert_ffn", "moe_expert_ffn_set_timing_events",
+    "moe_expert_ffn_workspace_bytes", "moe_expert_ffn", "moe_expert_ffn_timed",
     "moe_combine",
     "moe_route_topk", "moe_dispatch_topk", "moe_expert_ffn_rows", "moe_combine_topk",
     "moe_plan_dispatch_workspace_bytes", "moe_plan_dispatch",
@@ -48,19 +48,30 @@ class SruWeightsC(C.Structure):
 
 
 def lib():
-    """Load the built library (build it first if it was never built); fail loudly otherwise."""
+    """Load the built library (build it first if it was never built); fail loudly otherwise -- also when
+    the binary on disk was compiled from other sources than the ones beside it (no silent rebuild)."""
     global _lib
     if _lib is None:
+        from .build import build_library, source_id
         if not os.path.exists(LIB_PATH):
-            from .build import build_library
             build_library()
-        _lib = C.CDLL(LIB_PATH)
+        loaded = C.CDLL(LIB_PATH)
+        try:
+            loaded.moe_build_id.restype = C.c_char_p
+            built_from = loaded.moe_build_id().decode()
+        except AttributeError:
+            built_from = "none"
+        if built_from != source_id():
+            raise RuntimeError(
+                f"{LIB_PATH} was built from sources {built_from}, the sources here are {source_id()}: rebuild it "
+                "(python -m paper_2605_11537_amd.build)")
+        _lib = loaded
         _lib.moe_last_error.restype = C.c_char_p
         for n in EXPORTS:
             f = getattr(_lib, n)
             if n.endswith("_bytes"):
                 f.restype = C.c_size_t
-            elif n != "moe_last_error":
+            elif n not in ("moe_last_error", "moe_build_id"):
                 f.restype = C.c_int
         I, S, P = C.c_int, C.c_size_t, C.c_void_p
         _lib.moe_route_workspace_bytes.argtypes = [I, I, I, I]
@@ -75,7 +86,7 @@ def lib():
         _lib.moe_pack_weights.argtypes = [P, I, I, I, I, P, P]
         _lib.moe_expert_ffn_workspace_bytes.argtypes = [I, I, I, I, I]
         _lib.moe_expert_ffn.argtypes = [P, P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P]
-        _lib.moe_expert_ffn_set_timing_events.argtypes = [P, P, P]
+        _lib.moe_expert_ffn_timed.argtypes = [P, I, P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P, P, P, P]
         _lib.moe_combine.argtypes = [P, P, P, P, I, I, I, I, P, P]
         _lib.moe_route_topk.argtypes = [P, P, I, P, I, I, I, I, I, I, P, P, P, P, S, P]
         _lib.moe_dispatch_topk.argtypes = [P, P, P, I, I, I, I, I, I, I, P, P, P, P, P, P, P, P, P, S, P]
@@ -226,9 +237,11 @@ def moe_pack_weights(w, out=None):
 
 
 def moe_expert_ffn(x_perm, w1, w2, slot_offset, slot_expert, n_slots, E, F, max_slots=None,
-                   schedule=SCHEDULE_SLOTS, weight_layout=None, out=None, ws=None, row_index=None):
+                   schedule=SCHEDULE_SLOTS, weight_layout=None, out=None, ws=None, row_index=None, events=None):
     """-> y_perm [max_rows, d].  bf16 weights must already be packed (``moe_pack_weights``).
-    With row_index (moe_dispatch's perm), x_perm is the unpermuted token matrix (fused gather)."""
+    With row_index (moe_dispatch's perm), x_perm is the unpermuted token matrix (fused gather).
+    events (measurement only): three torch.cuda.Event objects (enable_timing=True, already created by a
+    first record()) recorded before, between and after the two products (moe_expert_ffn_timed)."""
     max_rows, d = x_perm.shape
     dev = x_perm.device
     dt = _dt(x_perm)
@@ -238,17 +251,16 @@ def moe_expert_ffn(x_perm, w1, w2, slot_offset, slot_expert, n_slots, E, F, max_
         max_slots = slot_expert.shape[0]
     y = out if out is not None else torch.empty_like(x_perm)
     ws = ws if ws is not None else _ws(lib().moe_expert_ffn_workspace_bytes(max_rows, max_slots, d, F, dt), dev)
+    if events is not None:
+        _check(lib().moe_expert_ffn_timed(_ptr(x_perm), max_rows, _ptr(row_index), _ptr(w1), _ptr(w2), weight_layout,
+                                          _ptr(slot_offset), _ptr(slot_expert), _ptr(n_slots), max_rows, max_slots, E,
+                                          d, F, dt, schedule, _ptr(y), _ptr(ws), ws.numel(), _stream(),
+                                          *[C.c_void_p(e.cuda_event) for e in events]))
+        return y
     _check(lib().moe_expert_ffn(_ptr(x_perm), _ptr(row_index), _ptr(w1), _ptr(w2), weight_layout, _ptr(slot_offset),
                                 _ptr(slot_expert), _ptr(n_slots), max_rows, max_slots, E, d, F, dt, schedule,
                                 _ptr(y), _ptr(ws), ws.numel(), _stream()))
     return y
-
-
-def set_ffn_timing_events(ev0, ev1, ev2):
-    """torch.cuda.Event objects (enable_timing=True, already created by a first record()) that the
-    next moe_expert_ffn call records around its two GEMM kernels."""
-    _check(lib().moe_expert_ffn_set_timing_events(C.c_void_p(ev0.cuda_event), C.c_void_p(ev1.cuda_event),
-                                                  C.c_void_p(ev2.cuda_event)))
 
 
 def moe_combine(y_perm, x, inv, expert_prob, residual=0, out=None):
@@ -333,7 +345,7 @@ def moe_dispatch_topk(x, expert_idx, replicas, E, slot_capacity, max_slots, out=
 
 
 def moe_expert_ffn_rows(x, row_index, max_rows, w1, w2, slot_offset, slot_expert, n_slots, E, F, max_slots=None,
-                        schedule=SCHEDULE_SLOTS, weight_layout=None, out=None, ws=None):
+                        schedule=SCHEDULE_SLOTS, weight_layout=None, out=None, ws=None, events=None):
     """moe_expert_ffn gathering its rows from x [n_x_rows, d] through row_index [max_rows]
     (moe_dispatch_topk's row_token).  -> y_perm [max_rows, d]."""
     n_x_rows, d = x.shape
@@ -345,9 +357,13 @@ def moe_expert_ffn_rows(x, row_index, max_rows, w1, w2, slot_offset, slot_expert
         max_slots = slot_expert.shape[0]
     y = out if out is not None else torch.empty(max_rows, d, dtype=x.dtype, device=dev)
     ws = ws if ws is not None else _ws(lib().moe_expert_ffn_workspace_bytes(max_rows, max_slots, d, F, dt), dev)
-    _check(lib().moe_expert_ffn_rows(_ptr(x), n_x_rows, _ptr(row_index), _ptr(w1), _ptr(w2), weight_layout,
-                                     _ptr(slot_offset), _ptr(slot_expert), _ptr(n_slots), max_rows, max_slots, E, d,
-                                     F, dt, schedule, _ptr(y), _ptr(ws), ws.numel(), _stream()))
+    args = (_ptr(x), n_x_rows, _ptr(row_index), _ptr(w1), _ptr(w2), weight_layout, _ptr(slot_offset),
+            _ptr(slot_expert), _ptr(n_slots), max_rows, max_slots, E, d, F, dt, schedule, _ptr(y), _ptr(ws),
+            ws.numel(), _stream())
+    if events is not None:
+        _check(lib().moe_expert_ffn_timed(*args, *[C.c_void_p(e.cuda_event) for e in events]))
+    else:
+        _check(lib().moe_expert_ffn_rows(*args))
     return y
 
 
@@ -386,8 +402,8 @@ class MoeLayerTopK:
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
 
     def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
-                out=None, router_layout=LAYOUT_PLAIN, marks=None):
-        """marks: as in MoeLayer.forward."""
+                out=None, router_layout=LAYOUT_PLAIN, marks=None, ffn_events=None):
+        """marks, ffn_events: as in MoeLayer.forward."""
         if marks is not None:
             marks[0].record()
         idx, wgt, _ = moe_route_topk(x, w_router, b_router, self.k, self.renormalize, out=self.route_out,
@@ -400,7 +416,7 @@ class MoeLayerTopK:
             marks[2].record()
         y = moe_expert_ffn_rows(x, dp["row_token"], self.k * self.T, w1, w2, dp["slot_offset"], pl["slot_expert"],
                                 pl["n_slots"], self.E, self.F, max_slots=self.max_slots, schedule=schedule,
-                                out=self.y_perm, ws=self.ffn_ws)
+                                out=self.y_perm, ws=self.ffn_ws, events=ffn_events)
         if marks is not None:
             marks[3].record()
         o = moe_combine_topk(y, x, dp["inv"], wgt, residual, out=self.out if out is None else out)
@@ -436,11 +452,12 @@ class MoeLayer:
         self.out = torch.empty(T, d, dtype=dtype, device=dev)
 
     def forward(self, x, w_router, b_router, w1, w2, plan_ids=None, schedule=SCHEDULE_SLOTS, residual=0,
-                out=None, router_layout=LAYOUT_PLAIN, fuse_gather=True, plan=None, marks=None):
+                out=None, router_layout=LAYOUT_PLAIN, fuse_gather=True, plan=None, marks=None, ffn_events=None):
         """plan: tables of a replica_plan call made earlier (e.g. by MoePipeline on another stream);
         otherwise the plan is computed here from plan_ids, or from the router's own ids.
         marks: five torch.cuda.Event objects recorded before the router and after each of the four
-        calls (router, plan + dispatch, expert FFN, combine), for per-call timing."""
+        calls (router, plan + dispatch, expert FFN, combine), for per-call timing.
+        ffn_events: three events recorded around the two products of the expert FFN (measurement only)."""
         if marks is not None:
             marks[0].record()
         idx, prob, _ = moe_route(x, w_router, b_router, out=self.route_out, ws=self.route_ws,
@@ -460,7 +477,8 @@ class MoeLayer:
             marks[2].record()
         y = moe_expert_ffn(x if fuse_gather else dp["x_perm"], w1, w2, dp["slot_offset"], pl["slot_expert"],
                            pl["n_slots"], self.E, self.F, max_slots=self.max_slots, schedule=schedule,
-                           out=self.y_perm, ws=self.ffn_ws, row_index=dp["perm"] if fuse_gather else None)
+                           out=self.y_perm, ws=self.ffn_ws, row_index=dp["perm"] if fuse_gather else None,
+                           events=ffn_events)
         if marks is not None:
             marks[3].record()
         o = moe_combine(y, x, dp["inv"], prob, residual, out=self.out if out is None else out)

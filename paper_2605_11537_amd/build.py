@@ -20,6 +20,20 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def source_id() -> str:
+    """Hash of everything the library is compiled from (csrc/*, include/*.h).  build_library() compiles it
+    into the library (moe_build_id()); binding.lib() refuses a library whose id differs from the sources
+    beside it, so a stale binary cannot be tested or timed by accident."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(CSRC, "*"))) + sorted(glob.glob(os.path.join(HERE, "..", "include", "*.h")))
+    for f in files:
+        if os.path.isfile(f):
+            h.update(os.path.basename(f).encode() + b"\0")
+            h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def build_library(verbose: bool = False) -> str:
     """One hipcc -c per source, side by side, then one link."""
     from concurrent.futures import ThreadPoolExecutor
@@ -27,7 +41,7 @@ def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     obj_dir = os.path.join(HERE, "_build")
     os.makedirs(obj_dir, exist_ok=True)
-    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"] + ["-c"]
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"] + ["-c", f'-DMOE_BUILD_ID="{source_id()}"']
 
     def run(cmd):
         if verbose:

@@ -16,4 +16,9 @@ void set_error(const char *fmt, ...)
 }  // namespace moe
 
 extern "C" const char *moe_last_error(void) { return moe::g_err; }
-extern "C" int moe_version(void) { return 100; }
+extern "C" int moe_version(void) { return 200; }
+
+#ifndef MOE_BUILD_ID
+#define MOE_BUILD_ID "unknown"
+#endif
+extern "C" const char *moe_build_id(void) { return MOE_BUILD_ID; }

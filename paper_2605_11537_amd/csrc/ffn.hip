@@ -333,9 +333,6 @@ static inline bool ffn_use_dense(int max_rows, int max_slots, int K, int N, int 
            (long long)max_rows >= 64LL * max_slots && max_rows >= 4096;
 }
 
-// events the next moe_expert_ffn call of this thread records around its two GEMM kernels
-static thread_local hipEvent_t g_timing_ev[3] = {nullptr, nullptr, nullptr};
-
 }  // namespace moe
 
 using namespace moe;
@@ -361,14 +358,6 @@ extern "C" int moe_pack_weights(const void *w, int E, int K, int N, int dtype, v
     return MOE_OK;
 }
 
-extern "C" int moe_expert_ffn_set_timing_events(void *before_gemm1, void *between, void *after_gemm2)
-{
-    g_timing_ev[0] = (hipEvent_t)before_gemm1;
-    g_timing_ev[1] = (hipEvent_t)between;
-    g_timing_ev[2] = (hipEvent_t)after_gemm2;
-    return MOE_OK;
-}
-
 extern "C" size_t moe_expert_ffn_workspace_bytes(int max_rows, int max_slots, int d, int F, int dtype)
 {
     if (max_rows < 0 || max_slots <= 0 || d <= 0 || F <= 0) return 0;
@@ -385,7 +374,7 @@ static int expert_ffn_checked(const void *x_perm, int n_x_rows, const int32_t *r
                               const void *w2, int weight_layout, const int32_t *slot_offset,
                               const int32_t *slot_expert, const int32_t *n_slots, int max_rows, int max_slots, int E,
                               int d, int F, int dtype, int schedule, void *y_perm, void *ws, size_t ws_bytes,
-                              void *stream)
+                              void *stream, void *const *timing_events = nullptr)
 {
     MOE_REQUIRE(max_rows >= 0 && max_slots > 0 && E > 0 && d > 0 && F > 0, MOE_ERR_INVALID_ARG,
                 "moe_expert_ffn: max_rows=%d max_slots=%d E=%d d=%d F=%d out of range", max_rows, max_slots, E, d,
@@ -454,8 +443,10 @@ static int expert_ffn_checked(const void *x_perm, int n_x_rows, const int32_t *r
     int grid_items = schedule != MOE_SCHEDULE_SLOTS ? (max_slots < max_items ? max_slots : max_items)
                      : (dense || listless)          ? max_slots
                                                     : max_slots + max_rows / tile_rows + 1;
-    hipEvent_t ev[3] = {g_timing_ev[0], g_timing_ev[1], g_timing_ev[2]};
-    g_timing_ev[0] = g_timing_ev[1] = g_timing_ev[2] = nullptr;
+    // measurement only (moe_expert_ffn_timed): events recorded before, between and after the two products
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    if (timing_events)
+        for (int i = 0; i < 3; ++i) ev[i] = (hipEvent_t)timing_events[i];
     if (ev[0]) (void)hipEventRecord(ev[0], st);
     if (dtype == MOE_BF16) {
         // worst case of both orders: chunks of FFN_GROUP items, rounded up to 8 chunks
@@ -542,4 +533,17 @@ extern "C" int moe_expert_ffn_rows(const void *x, int n_x_rows, const int32_t *r
                 "moe_expert_ffn_rows: n_x_rows=%d out of range or null row_index", n_x_rows);
     return expert_ffn_checked(x, n_x_rows, row_index, w1, w2, weight_layout, slot_offset, slot_expert, n_slots,
                               max_rows, max_slots, E, d, F, dtype, schedule, y_perm, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_expert_ffn_timed(const void *x, int n_x_rows, const int32_t *row_index, const void *w1,
+                                    const void *w2, int weight_layout, const int32_t *slot_offset,
+                                    const int32_t *slot_expert, const int32_t *n_slots, int max_rows, int max_slots,
+                                    int E, int d, int F, int dtype, int schedule, void *y_perm, void *ws,
+                                    size_t ws_bytes, void *stream, void *ev_before, void *ev_between, void *ev_after)
+{
+    MOE_REQUIRE(n_x_rows >= 0 && (row_index || n_x_rows == max_rows), MOE_ERR_INVALID_ARG,
+                "moe_expert_ffn_timed: n_x_rows=%d must equal max_rows=%d without row_index", n_x_rows, max_rows);
+    void *const evs[3] = {ev_before, ev_between, ev_after};
+    return expert_ffn_checked(x, n_x_rows, row_index, w1, w2, weight_layout, slot_offset, slot_expert, n_slots,
+                              max_rows, max_slots, E, d, F, dtype, schedule, y_perm, ws, ws_bytes, stream, evs);
 }

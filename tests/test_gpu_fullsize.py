@@ -1,9 +1,9 @@
 """Full-size GPU parity on the large workloads, in the launch configuration bench.py times.
 
-The oracle cannot evaluate these sizes whole in test time, so: integer stages (plan, dispatch)
-are compared bit for bit at full size against the oracle fed the GPU's own router ids; float
-stages are compared on sampled rows / tokens that the oracle evaluates one by one; and
-size-independent properties (conservation, no drops, passthrough) are checked on everything.
+Integer stages (plan, dispatch) are compared bit for bit against the oracle fed the GPU's own router
+ids; the float stages are compared on every kept row and every token (the oracle evaluates the whole
+layer: a second or so at 16384 tokens, several seconds per layer at 65536); size-independent properties
+(conservation, no drops, passthrough, slot schedule == expert schedule bit for bit) are checked as well.
 """
 import time
 
@@ -27,6 +27,14 @@ def _integer_parity(moe, layer, idx_host, E, C, R, T, plan_ids=None):
     for k in ("counts", "kept", "expert_offset", "slot_offset", "perm", "inv"):
         assert (to_host(layer.disp_out[k]) == dp[k]).all(), k
     return pl, dp
+
+
+def _assert_rows_close(got, ref, what):
+    """Element-wise bound, so that one bad row cannot hide behind the tensor's maximum: half a bf16 ulp
+    of the value for its one rounding, plus accumulation-order noise relative to the tensor's scale."""
+    g, r = f64(got), f64(ref)
+    bad = np.abs(g - r) > 2.0 ** -7 * np.abs(r) + 1e-3 * np.abs(r).max()
+    assert not bad.any(), f"{what}: {int(bad.sum())} elements off, first at row {int(np.argwhere(bad)[0][0])}"
 
 
 @pytest.mark.timeout(600)
@@ -55,18 +63,14 @@ def test_workload4_full_size(cap_key):
     got = to_host(out)
     dropped = dp["inv"] < 0
     assert (got[dropped] == c["x"][dropped]).all()
-    # sampled rows: include the first and last rows of the hottest expert and the global tail
-    rng = np.random.default_rng(4)
-    hot = int(np.argmax(dp["kept"]))
-    rows = np.unique(np.concatenate([rng.choice(K, 80, replace=False), [0, K - 1, dp["expert_offset"][hot],
-                                     dp["expert_offset"][hot + 1] - 1]])).astype(np.int32)
+    # every kept row of the expert products and every token of the output
     xp = np.zeros_like(c["x"])
-    xp[rows] = c["x"][dp["perm"][rows]]
-    y = oracle.ffn(xp, c["w1"], c["w2"], dp["slot_offset"], pl["slot_expert"], pl["n_slots"], rows=rows)
-    assert_close(to_host(layer.y_perm)[rows], y[rows], synth.BF16, "y_perm sample")
+    xp[:K] = c["x"][dp["perm"][:K]]
+    y = oracle.ffn(xp, c["w1"], c["w2"], dp["slot_offset"], pl["slot_expert"], pl["n_slots"])
+    assert_close(to_host(layer.y_perm)[:K], y[:K], synth.BF16, "y_perm")
+    _assert_rows_close(to_host(layer.y_perm)[:K], y[:K], "y_perm")
     ref_out = oracle.combine(y, c["x"], dp["inv"], g_prob, 0)
-    toks = dp["perm"][rows]
-    assert_close(got[toks], ref_out[toks], synth.BF16, "out sample")
+    assert_close(got, ref_out, synth.BF16, "out")
     # replication off (same plan): identical outputs
     out_off = layer.forward(x, wr, b, w1, w2, schedule=moe.SCHEDULE_EXPERTS, router_layout=moe.LAYOUT_PACKED)
     assert torch.equal(out, out_off)
@@ -76,21 +80,23 @@ def test_workload4_full_size(cap_key):
 
 @pytest.mark.timeout(900)
 def test_workload5_stack_full_size():
-    """6-layer stack, T=65536, E=256, one expert at 50% load, nothing may drop.  Sampled tokens
-    are followed through all six layers by the oracle alone (with no drops a token's result
-    depends on the other tokens only through ranks)."""
+    """6-layer stack, T=65536, E=256, one expert at 50% load, nothing may drop.  The oracle follows the
+    whole batch through all six layers from its own state (the GPU contributes only the router's integer
+    decision and probability of each layer, which are checked first); every token of every layer's
+    output is compared, layer 0 also on every row of the second expert product.  Each layer is run a
+    second time with the expert schedule (the 128-column kernel alone) and must agree bit for bit with the
+    slot schedule (the persistent 256 x 256 tile kernel at this size) on all rows."""
     import paper_2605_11537_amd as moe
     t0 = time.time()
     c = synth.config_inputs(5, weights=False)
     T, d, F, E, R, C, NL = c["T"], c["d"], c["F"], c["E"], c["R"], c["C"], c["n_layers"]
     seed = synth.workloads.SEED0 + 5
     layer = moe.MoeLayer(T, d, F, E, R, C, torch.bfloat16)
-    rng = np.random.default_rng(5)
-    sample = np.sort(rng.choice(T, 24, replace=False))
-    ref_x = c["x"][sample].copy()                      # oracle-side state of the sampled tokens
+    ref_x = c["x"].copy()                              # oracle-side state of the whole batch
     cur = to_dev(c["x"])
     nxt = torch.empty_like(cur)
-    hot_rows_seen = 0
+    nxt_off = torch.empty_like(cur)
+    most_slots = 0
     for l in range(NL):
         lay = c["layers"][l]
         w1h = synth.normal_tensor((E, d, F), 0.02, [seed, 50 + l], synth.BF16)
@@ -99,27 +105,34 @@ def test_workload5_stack_full_size():
         wr = to_dev(lay["w_router"])
         layer.forward(cur, wr, None, w1, w2, residual=1, out=nxt)
         torch.cuda.synchronize()
+        y_on = layer.y_perm.clone()
         g_idx, g_prob = to_host(layer.route_out[0]), to_host(layer.route_out[1])
         pl, dp = _integer_parity(moe, layer, g_idx, E, C, R, T)
         assert int(dp["expert_offset"][E]) == T and (dp["inv"] >= 0).all()      # nothing drops
         n = dp["counts"]
         assert n.max() >= 0.49 * T                                              # the hot expert
-        hot_rows_seen = max(hot_rows_seen, int(pl["replicas"].max()))
-        # sampled tokens, one by one, from the oracle's own previous-layer state
+        most_slots = max(most_slots, int(pl["replicas"].max()))
+        layer.forward(cur, wr, None, w1, w2, residual=1, out=nxt_off, schedule=moe.SCHEDULE_EXPERTS)
+        torch.cuda.synchronize()
+        assert torch.equal(y_on, layer.y_perm), f"layer {l}: tile kernel and 128-column kernel disagree"
+        assert torch.equal(nxt, nxt_off)
+        # the oracle on its own state: router decision first, then the layer under the GPU's ids
         rt = oracle.route(ref_x, lay["w_router"], None)
         tau = 1e-4 * max(1.0, np.abs(rt["logits"]).max())
-        check_ids_margin(g_idx[sample], rt["idx"], rt["idx2"], rt["margin"], tau, f"layer {l} route")
-        new_ref = np.empty_like(ref_x)
-        for i in range(sample.size):
-            e = int(g_idx[sample[i]])
-            y = oracle.ffn(ref_x[i:i + 1], w1h, w2h, np.array([0, 1], np.int32), np.array([e], np.int32), 1)
-            new_ref[i] = oracle.combine(y, ref_x[i:i + 1], np.array([0], np.int32),
-                                        g_prob[sample[i]:sample[i] + 1], 1)[0]
-        ref_x = new_ref
-        got = to_host(nxt[torch.from_numpy(sample).cuda()])
-        assert_close(got, ref_x, synth.BF16, f"layer {l} sampled tokens")
+        flips = check_ids_margin(g_idx, rt["idx"], rt["idx2"], rt["margin"], tau, f"layer {l} route")
+        same = g_idx == rt["idx"]
+        # layer 0 reads the same bits on both sides; later layers read states that differ by the bf16
+        # roundings accumulated so far, so their gate probabilities agree less closely
+        assert np.abs(g_prob - rt["prob"])[same].max() <= (1e-4 if l == 0 else 1e-2)
+        xp = ref_x[dp["perm"]]
+        y = oracle.ffn(xp, w1h, w2h, dp["slot_offset"], pl["slot_expert"], pl["n_slots"])
+        if l == 0:                       # same inputs on both sides here: the product itself, row by row
+            assert_close(to_host(y_on), y, synth.BF16, "layer 0 y_perm")
+            _assert_rows_close(to_host(y_on), y, "layer 0 y_perm")
+        ref_x = oracle.combine(y, ref_x, dp["inv"], g_prob, 1)
+        assert_close(to_host(nxt), ref_x, synth.BF16, f"layer {l} out")
         cur, nxt = nxt, cur
         del w1, w2, w1h, w2h
         print(f"workload 5 layer {l}: slots {pl['n_slots']}, hot expert {n.max()} tokens in "
-              f"{pl['replicas'].max()} slots, t={time.time() - t0:.1f}s", flush=True)
-    assert hot_rows_seen >= 32          # ceil(32768 / 1024) slots for the hot expert
+              f"{pl['replicas'].max()} slots, {flips} near-tie flips, t={time.time() - t0:.1f}s", flush=True)
+    assert most_slots >= 32             # ceil(32768 / 1024) slots for the hot expert

@@ -282,6 +282,43 @@ def test_ffn_bf16_long_slots(schedule):
     assert torch.equal(y[:K], y2[:K])
 
 
+@pytest.mark.parametrize("case", ["ragged", "long", "dense"])
+def test_ffn_first_product_h(case):
+    """The first product on its own: h = relu(x_perm W1[e]) as left in the head of the workspace, element by
+    element against the oracle, for the three kernels that can write it (64/128-row tiles of the 128-column
+    kernel reading the slot tables, the same with a work list, the 256 x 256 tile kernel)."""
+    if case == "ragged":
+        E, d, F = 5, 128, 256
+        rows, experts = [3, 0, 64, 65, 1, 130, 40, 0, 17], [0, 0, 1, 2, 2, 3, 3, 3, 4]
+    elif case == "long":
+        E, d, F = 3, 256, 512
+        rows, experts = [300, 129, 0, 128, 1, 700], [0, 0, 1, 1, 2, 2]
+    else:
+        E, d, F = 4, 256, 512
+        rows, experts = [1500, 129, 0, 256, 257, 1, 385, 2000, 63], [0, 0, 1, 1, 2, 2, 3, 3, 3]
+    so, se = _slots_for(rows, experts)
+    K = int(so[-1])
+    T = K + 9
+    x = synth.normal_tensor((T, d), 1.0, [51], synth.BF16)
+    w1 = synth.normal_tensor((E, d, F), 0.05, [52], synth.BF16)
+    w2 = synth.normal_tensor((E, F, d), 0.05, [53], synth.BF16)
+    ref_y, ref_h = oracle.ffn(x, w1, w2, so, se, len(rows), want_h=True)
+    ws = torch.zeros(moe.lib().moe_expert_ffn_workspace_bytes(T, len(rows), d, F, moe.MOE_BF16), dtype=torch.uint8,
+                     device="cuda")
+    y = moe.moe_expert_ffn(to_dev(x), moe.moe_pack_weights(to_dev(w1)), moe.moe_pack_weights(to_dev(w2)),
+                           to_dev(so), to_dev(se), torch.tensor([len(rows)], dtype=torch.int32, device="cuda"),
+                           E, F, ws=ws)
+    _sync()
+    h = to_host(ws[:T * F * 2].view(torch.bfloat16).view(T, F))
+    assert (f64(ref_h[:K]) > 0).mean() > 0.3 and (f64(ref_h[:K]) == 0).mean() > 0.3    # the ReLU cuts about half
+    assert_close(h[:K], ref_h[:K], synth.BF16, "h")
+    g, r = f64(h[:K]), f64(ref_h[:K])
+    assert (np.abs(g - r) <= 2.0 ** -7 * np.abs(r) + 1e-3 * np.abs(r).max()).all()
+    assert ((g == 0) == (r == 0)).mean() > 0.999           # zeros of the ReLU in the same places (up to rounding at 0)
+    assert (h[K:] == 0).all()                              # rows outside all slots are not written
+    assert_close(to_host(y)[:K], ref_y[:K], synth.BF16, "y")
+
+
 def test_ffn_bf16_dense_tiles():
     """Enough rows that the 256 x 256 tile kernel takes the slots: lengths around its cut points
     (pieces of 1..256 rows use 1..8 row blocks of the tile), short and empty slots beside them, and
@@ -425,10 +462,8 @@ def test_replication_on_and_off_give_identical_outputs_config2():
     c = synth.config_inputs(2)
     layer, out_on, packed = _run_layer_gpu(c, c["C"], c["R"], schedule=0)
     on = out_on.clone()
-    rng = np.random.default_rng(2)
     K = int(layer.disp_out["expert_offset"][c["E"]].item())
-    rows = np.sort(rng.choice(K, size=96, replace=False)).astype(np.int32)
-    flips, _ = _compare_layer(c, c["C"], c["R"], layer, on, rows=rows)
+    flips, _ = _compare_layer(c, c["C"], c["R"], layer, on)          # every kept row, every token
     print(f"config 2: {flips} near-tie flips, K={K}", flush=True)
     layer2, out_off, _ = _run_layer_gpu(c, c["C"], c["R"], schedule=1, packed=packed)
     assert torch.equal(on, out_off)
@@ -436,7 +471,7 @@ def test_replication_on_and_off_give_identical_outputs_config2():
     layer3, out_plain, _ = _run_layer_gpu(c, c["C"], 0, packed=packed)
     K0 = int(layer3.disp_out["expert_offset"][c["E"]].item())
     assert K0 < K
-    _compare_layer(c, c["C"], 0, layer3, out_plain, rows=rows[rows < K0][:32])
+    _compare_layer(c, c["C"], 0, layer3, out_plain)
 
 
 def test_replication_invariance_no_drops():
@@ -444,14 +479,17 @@ def test_replication_invariance_no_drops():
     c = synth.moe_layer_inputs(1500, 128, 256, 16, synth.BF16, 1.2, 123)
     layer_a, out_a, packed = _run_layer_gpu(c, 1500, 0)
     a = out_a.clone()
-    forged = to_dev((np.arange(1500) % 3).astype(np.int32))
-    layer_b, out_b, _ = _run_layer_gpu(c, 100, 40, plan_ids=forged, packed=packed)
-    kept_b = int(layer_b.disp_out["expert_offset"][16].item())
-    if kept_b == 1500:
-        assert torch.equal(a, out_b)
     hot = int(layer_a.plan_out["plan_counts"].argmax().item())
     n_hot = int(layer_a.plan_out["plan_counts"].max().item())
     assert n_hot <= 700
+    # a forged prediction (two experts, 750 ids each -> a second slot for both) is wrong about the load;
+    # the slot capacity is chosen so that one slot already holds the busiest expert, so nothing may
+    # drop whatever the plan hands out, and the outputs must not move
+    forged = to_dev((np.arange(1500) % 2).astype(np.int32))
+    layer_b, out_b, _ = _run_layer_gpu(c, 700, 40, plan_ids=forged, packed=packed)
+    assert to_host(layer_b.plan_out["replicas"]).tolist() == [2, 2] + [1] * 14
+    assert int(layer_b.disp_out["expert_offset"][16].item()) == 1500
+    assert torch.equal(a, out_b)
     all_hot = torch.full((1500,), hot, dtype=torch.int32, device="cuda")
     layer_c, out_c, _ = _run_layer_gpu(c, 700, 9, plan_ids=all_hot, packed=packed)
     assert int(layer_c.plan_out["replicas"][hot].item()) == 3      # ceil(1500/700) slots

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import synth
-from gpu_util import to_dev, to_host
+from gpu_util import assert_close, check_ids_margin, to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -15,21 +15,32 @@ def _weights(moe, s):
                           [to_dev(b) for b in s["b_r"]], to_dev(s["w_head"]), to_dev(s["b_head"]))
 
 
+# Fixed in advance, independent of what a run measures: the logits may be off by at most
+# LOGIT_TOL * max|logit| (activations are rounded to bf16 between layers; the matrix cores sum in binary32 in
+# another order), the argmax must equal the oracle's wherever its top-2 gap exceeds TAU * max|logit| and be the
+# runner-up otherwise, and at most MAX_FLIPS of the predictions may be such near-ties.
+LOGIT_TOL = 5e-3
+TAU = 5e-3
+MAX_FLIPS = 0.005
+
+
+def _check_prediction(got, lg, ref, what):
+    scale = np.abs(ref["logits"]).max()
+    err = np.abs(lg - ref["logits"]).max()
+    assert err <= LOGIT_TOL * scale, f"{what}: logits off by {err / scale:.3e} of the scale"
+    flips = check_ids_margin(got, ref["pred"], ref["idx2"], ref["margin"], TAU * scale, what)
+    assert flips <= max(1, int(MAX_FLIPS * got.size)), f"{what}: {flips} of {got.size} predictions differ"
+    return err, scale, flips
+
+
 def _compare(moe, s, what):
     ref = oracle.sru(s["emb"], s["w_cat"], s["b_f"], s["b_r"], s["w_head"], s["b_head"])
     pred, logits = moe.sru_predict(to_dev(s["emb"]), _weights(moe, s), want_logits=True)
     torch.cuda.synchronize()
     lg = to_host(logits).astype(np.float64)
-    scale = np.abs(ref["logits"]).max()
-    err = np.abs(lg - ref["logits"]).max()
-    # activations are stored as bf16 between layers: the bf16 bar applies to the logits
-    assert err <= 2e-2 * scale, f"{what}: logits off by {err / scale:.3e}"
-    # the argmax may differ only where the oracle's top-2 gap is inside twice that error
     got = to_host(pred)
+    err, scale, flips = _check_prediction(got, lg, ref, what)
     diff = got != ref["pred"]
-    assert not (diff & (ref["margin"] > 2 * err)).any()
-    assert (got[diff] == ref["idx2"][diff]).all()
-    assert diff.mean() <= 0.02, f"{what}: {diff.mean():.3%} of predictions differ"
     print(f"{what}: max logit err {err:.2e} (scale {scale:.2f}), {int(diff.sum())} near-tie flips", flush=True)
     if s["n_out"] in (128, 256):
         # weights packed once by the caller: same kernels, same bits
@@ -64,8 +75,8 @@ def test_sru_small(B, L, n_in, n_h, layers, n_out, bias):
     (8, 100, 128, 256, 1, 8),        # a multiple of 8 sequences: whole sequences per XCD in the attention kernel
 ])
 def test_sru_with_sparsemax_attention(B, L, n_in, n_h, layers, n_out):
-    """The attention variant of the predictor against the oracle: the attended states z element by
-    element (bf16 bar), then logits and predictions with the same near-tie rule as without it."""
+    """The attention variant of the predictor against the oracle: logits and predictions under the same
+    fixed bounds and near-tie rule as without it."""
     import paper_2605_11537_amd as moe
     s = synth.sru_inputs(B, L, n_in, n_h, layers, n_out, synth.BF16, 700 + L, bias_std=0.2, w_std=0.08)
     ref = oracle.sru_attention(s["emb"], s["w_cat"], s["b_f"], s["b_r"], s["w_head"], s["b_head"])
@@ -74,14 +85,9 @@ def test_sru_with_sparsemax_attention(B, L, n_in, n_h, layers, n_out):
     pred, logits = moe.sru_predict(to_dev(s["emb"]), w, want_logits=True)
     torch.cuda.synchronize()
     lg = to_host(logits).astype(np.float64)
-    scale = np.abs(ref["logits"]).max()
-    err = np.abs(lg - ref["logits"]).max()
-    assert err <= 2e-2 * scale, f"attention logits off by {err / scale:.3e}"
     got = to_host(pred)
+    err, scale, flips = _check_prediction(got, lg, ref, f"attention B={B} L={L}")
     diff = got != ref["pred"]
-    assert not (diff & (ref["margin"] > 2 * err)).any()
-    assert (got[diff] == ref["idx2"][diff]).all()
-    assert diff.mean() <= 0.02
     # without the attention the same weights give different logits (the option is really on)
     w0 = moe.SruWeights([to_dev(a) for a in s["w_cat"]], [to_dev(a) for a in s["b_f"]], [to_dev(a) for a in s["b_r"]],
                         to_dev(s["w_head"]), to_dev(s["b_head"]))
@@ -108,18 +114,18 @@ def test_sru_config3_and_predictor_driven_layer():
     assert (g_idx == rt["idx"]).mean() > 0.9999
     agree = (rt["idx"] == ref["pred"]).mean()
     assert 0.82 <= agree <= 0.90, agree                      # ~85% agreement by construction
-    rng = np.random.default_rng(0)
     K = int(layer.disp_out["expert_offset"][E].item())
-    rows = np.sort(rng.choice(K, size=64, replace=False)).astype(np.int32)
+    # every kept row and every token, the oracle planning from the same predicted ids
     full = oracle.layer(c["x"], c["w_router"], c["b_router"], c["w1"], c["w2"], C, R, idx=g_idx, prob=g_prob,
-                        plan_ids=got, rows=rows)
+                        plan_ids=got)
     assert (to_host(layer.plan_out["replicas"]) == full["plan"]["replicas"]).all()
     for k in ("counts", "kept", "expert_offset", "slot_offset", "perm", "inv"):
         assert (to_host(layer.disp_out[k]) == full["dispatch"][k]).all(), k
-    toks = full["dispatch"]["perm"][rows]
-    g = synth.storage_to_f64(to_host(out))[toks]
-    r = synth.storage_to_f64(full["out"])[toks]
-    assert np.abs(g - r).max() <= 2e-2 * np.abs(r).max()
+    assert K == int(full["dispatch"]["expert_offset"][E])
+    assert_close(to_host(layer.y_perm)[:K], full["y_perm"][:K], synth.BF16, "config 3 y_perm")
+    assert_close(to_host(out), full["out"], synth.BF16, "config 3 out")
+    dropped = full["dispatch"]["inv"] < 0
+    assert (to_host(out)[dropped] == c["x"][dropped]).all()
     print(f"config 3: router/predictor agreement {agree:.3f}, kept {K}/{T}", flush=True)
 
 
@@ -159,5 +165,22 @@ def test_two_stream_pipeline_equals_sequential():
     torch.cuda.synchronize()
     for i in range(n_batches):
         assert torch.equal(outs[i], seq[i]), f"batch {i}"
+    # against the definition, not only against the one-stream order: the oracle runs predictor, plan and layer
+    # of the first batch, of one in the middle and of the last (the router's ids and probabilities taken from
+    # a one-stream run of the library, the predictor's ids under the fixed near-tie rule)
+    for i in (0, 3, n_batches - 1):
+        emb_h, x_h = to_host(embs[i]), to_host(xs[i])
+        ref_p = oracle.sru(emb_h, s["w_cat"], s["b_f"], s["b_r"], s["w_head"], s["b_head"])
+        ids_g, lg_g = moe.sru_predict(embs[i], w, want_logits=True)
+        _check_prediction(to_host(ids_g), to_host(lg_g).astype(np.float64), ref_p, f"pipeline batch {i}")
+        r_idx, r_prob, _ = moe.moe_route(xs[i], wr, b)
+        rt = oracle.route(x_h, c["w_router"], c["b_router"])
+        check_ids_margin(to_host(r_idx), rt["idx"], rt["idx2"], rt["margin"],
+                         1e-4 * max(1.0, np.abs(rt["logits"]).max()), f"pipeline batch {i} route")
+        ref = oracle.layer(x_h, c["w_router"], c["b_router"], c["w1"], c["w2"], C, R, idx=to_host(r_idx),
+                           prob=to_host(r_prob), plan_ids=to_host(ids_g))
+        assert_close(to_host(outs[i]), ref["out"], synth.BF16, f"pipeline batch {i} out")
+        dropped = ref["dispatch"]["inv"] < 0
+        assert dropped.any() and (to_host(outs[i])[dropped] == x_h[dropped]).all()
     with pytest.raises(RuntimeError):
         pipe.forward(xs[0], wr, b, w1, w2)                  # nothing predicted is waiting
