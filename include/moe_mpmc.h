@@ -205,6 +205,23 @@ int moe_dispatch(const void *x, const int32_t *expert_idx, const int32_t *replic
                  int32_t *inv, void *x_perm, void *ws, size_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
+ * moe_dispatch_static -- moe_dispatch for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, outputs
+ * and kernels, but the per-block histograms live in a static device array of the library (1 MiB on
+ * every GPU the library runs on, held until the process ends) instead of a caller's workspace.
+ * Limit: ceil(T/1024) * E <= 262144 table entries (e.g. T <= 1048576 at E = 256); beyond it
+ * MOE_ERR_UNSUPPORTED.  The call allocates and frees nothing; the first call on a device asks the
+ * runtime for the array's address on that device (make one call outside any graph capture first).
+ * Nothing in the array has to be cleared between calls (every entry read was written by the same
+ * call).  All calls on one GPU share that GPU's array: calls that overlap on one GPU (different
+ * streams, or different host threads without ordering) race; order them or use moe_dispatch.
+ */
+int moe_dispatch_static(const void *x, const int32_t *expert_idx, const int32_t *replicas, int T, int d,
+                        int E, int slot_capacity, int max_slots, int dtype, int32_t *counts,
+                        int32_t *kept, int32_t *expert_offset, int32_t *slot_offset, int32_t *perm,
+                        int32_t *inv, void *x_perm, void *stream);
+
+/* ---------------------------------------------------------------------------------------
  * moe_plan_dispatch -- replica_plan (Algorithm 1 with the budget cap) on plan_idx[n_plan], then the
  * index tables of moe_dispatch (moe_dispatch_topk for k > 1) for expert_idx[k*T] under that plan, as
  * one call: the same tables, bit for bit, as the two calls with max_slots = E + budget and no row

@@ -25,7 +25,7 @@ EXPORTS = (
     "moe_route_workspace_bytes", "moe_route",
     "sru_predict_workspace_bytes", "sru_predict",
     "replica_plan_workspace_bytes", "replica_plan",
-    "moe_dispatch_workspace_bytes", "moe_dispatch",
+    "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_dispatch_static",
     "moe_packed_weights_bytes", "moe_pack_weights",
     "moe_expert_ffn_workspace_bytes", "moe_expert_ffn", "moe_expert_ffn_timed",
     "moe_combine",
@@ -82,6 +82,7 @@ def lib():
         _lib.replica_plan.argtypes = [P, I, I, I, I, I, P, P, P, P, P, P, S, P]
         _lib.moe_dispatch_workspace_bytes.argtypes = [I, I]
         _lib.moe_dispatch.argtypes = [P, P, P, I, I, I, I, I, I, P, P, P, P, P, P, P, P, S, P]
+        _lib.moe_dispatch_static.argtypes = [P, P, P, I, I, I, I, I, I, P, P, P, P, P, P, P, P]
         _lib.moe_packed_weights_bytes.argtypes = [I, I, I, I]
         _lib.moe_pack_weights.argtypes = [P, I, I, I, I, P, P]
         _lib.moe_expert_ffn_workspace_bytes.argtypes = [I, I, I, I, I]
@@ -226,6 +227,19 @@ def moe_dispatch(x, expert_idx, replicas, E, slot_capacity, max_slots, out=None,
                               _ptr(o["counts"]), _ptr(o["kept"]), _ptr(o["expert_offset"]), _ptr(o["slot_offset"]),
                               _ptr(o["perm"]), _ptr(o["inv"]), _ptr(xp), _ptr(ws), ws.numel(), _stream()))
     return o
+
+
+def moe_dispatch_static(x, expert_idx, replicas, E, slot_capacity, max_slots, out, shape=None, dtype=None):
+    """moe_dispatch without a workspace (the library's static scratch array): ``out`` must hold every
+    output tensor (the dict of ``moe_dispatch``), so that nothing is allocated here either."""
+    T, d = x.shape if x is not None else shape
+    dt = _dt(x) if x is not None else (MOE_BF16 if dtype == torch.bfloat16 else MOE_F32)
+    xp = out["x_perm"] if x is not None else None
+    _check(lib().moe_dispatch_static(_ptr(x), _ptr(expert_idx), _ptr(replicas), T, d, E, slot_capacity, max_slots,
+                                     dt, _ptr(out["counts"]), _ptr(out["kept"]), _ptr(out["expert_offset"]),
+                                     _ptr(out["slot_offset"]), _ptr(out["perm"]), _ptr(out["inv"]), _ptr(xp),
+                                     _stream()))
+    return out
 
 
 def moe_pack_weights(w, out=None):

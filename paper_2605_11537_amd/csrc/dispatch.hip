@@ -10,6 +10,8 @@
 //            (LDS table) + rank inside the chunk (wavefront ballots, one per id bit);
 //            writes inv / perm
 //   gather   whole-chip copy of the kept rows, x_perm[pos] = x[perm[pos]], 16-byte accesses
+#include <mutex>
+
 #include "plan_alloc.h"
 #include "route.h"
 
@@ -310,6 +312,38 @@ int dispatch_planned_launch(const int32_t *expert_idx, int T, int n_tokens, int 
     return MOE_OK;
 }
 
+// ------------------------------------------------------------------ allocation-free variant
+// The per-block histograms of moe_dispatch_static live in this file-scope device array instead of a
+// caller's workspace.  Every GPU the library runs on holds its own copy at its own address until the
+// process ends.  In host code the array's name is only a stand-in for the symbol: its device address is
+// asked of the runtime once per device and that pointer is what the kernels get.
+constexpr size_t DSP_STATIC_BYTES = (size_t)1 << 20;   // 262144 table entries: e.g. 256 blocks x 1024 experts
+static __device__ __align__(256) int32_t scratch[DSP_STATIC_BYTES / sizeof(int32_t)];
+
+constexpr int DSP_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static int32_t *g_scratch_ptr[DSP_MAX_DEVICES];        // device address of `scratch` per device ordinal
+
+static int32_t *static_scratch_of_current_device(const char *who)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= DSP_MAX_DEVICES) {
+        set_error("%s: cannot tell the current device (ordinal %d, at most %d devices)", who, dev, DSP_MAX_DEVICES);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_error("%s: hipGetSymbolAddress(scratch) failed on device %d: %s", who, dev, hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = (int32_t *)p;
+    }
+    return g_scratch_ptr[dev];
+}
+
 }  // namespace moe
 
 using namespace moe;
@@ -325,7 +359,8 @@ extern "C" size_t moe_dispatch_workspace_bytes(int T, int E)
 static int dispatch_checked(const char *who, const void *x, const int32_t *expert_idx, const int32_t *replicas, int T,
                             int n_tokens, int d, int E, int slot_capacity, int max_slots, int dtype, int32_t *counts,
                             int32_t *kept, int32_t *expert_offset, int32_t *slot_offset, int32_t *perm, int32_t *inv,
-                            int32_t *row_token, void *x_perm, void *ws, size_t ws_bytes, void *stream)
+                            int32_t *row_token, void *x_perm, void *ws, size_t ws_bytes, void *stream,
+                            bool static_scratch = false)
 {
     MOE_REQUIRE(T >= 0 && d > 0 && E > 0 && slot_capacity >= 1 && max_slots >= 0, MOE_ERR_INVALID_ARG,
                 "%s: T=%d d=%d E=%d slot_capacity=%d max_slots=%d out of range", who, T, d, E, slot_capacity,
@@ -342,8 +377,17 @@ static int dispatch_checked(const char *who, const void *x, const int32_t *exper
     MOE_REQUIRE(((size_t)d * esz) % 16 == 0, MOE_ERR_INVALID_ARG, "%s: row size %zu bytes is not a multiple of 16",
                 who, (size_t)d * esz);
     MOE_REQUIRE(aligned16(x) && aligned16(x_perm), MOE_ERR_INVALID_ARG, "%s: x / x_perm misaligned", who);
-    MOE_REQUIRE(ws && ws_bytes >= moe_dispatch_workspace_bytes(T, E), MOE_ERR_WORKSPACE,
-                "%s: workspace of %zu bytes needed, %zu given", who, moe_dispatch_workspace_bytes(T, E), ws_bytes);
+    if (static_scratch) {
+        MOE_REQUIRE(moe_dispatch_workspace_bytes(T, E) <= DSP_STATIC_BYTES, MOE_ERR_UNSUPPORTED,
+                    "%s: ceil(T/1024)*E = %zu table entries exceed the %zu of the static scratch array "
+                    "(use moe_dispatch with a workspace)",
+                    who, moe_dispatch_workspace_bytes(T, E) / sizeof(int32_t), DSP_STATIC_BYTES / sizeof(int32_t));
+        ws = static_scratch_of_current_device(who);
+        if (!ws) return MOE_ERR_HIP;
+    } else {
+        MOE_REQUIRE(ws && ws_bytes >= moe_dispatch_workspace_bytes(T, E), MOE_ERR_WORKSPACE,
+                    "%s: workspace of %zu bytes needed, %zu given", who, moe_dispatch_workspace_bytes(T, E), ws_bytes);
+    }
     hipStream_t st = (hipStream_t)stream;
     int nb = ceil_div(T, DSP_TOKENS);
     int32_t *block_hist = (int32_t *)ws;
@@ -390,4 +434,14 @@ extern "C" int moe_dispatch_topk(const void *x, const int32_t *expert_idx, const
     return dispatch_checked("moe_dispatch_topk", x, expert_idx, replicas, T * k, T, d, E, slot_capacity, max_slots,
                             dtype, counts, kept, expert_offset, slot_offset, perm, inv, row_token, x_perm, ws, ws_bytes,
                             stream);
+}
+
+extern "C" int moe_dispatch_static(const void *x, const int32_t *expert_idx, const int32_t *replicas, int T, int d,
+                                   int E, int slot_capacity, int max_slots, int dtype, int32_t *counts,
+                                   int32_t *kept, int32_t *expert_offset, int32_t *slot_offset, int32_t *perm,
+                                   int32_t *inv, void *x_perm, void *stream)
+{
+    return dispatch_checked("moe_dispatch_static", x, expert_idx, replicas, T, T, d, E, slot_capacity, max_slots,
+                            dtype, counts, kept, expert_offset, slot_offset, perm, inv, nullptr, x_perm, nullptr, 0,
+                            stream, true);
 }
