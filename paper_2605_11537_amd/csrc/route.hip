@@ -9,6 +9,7 @@
 //     experts, binary32 FMA in ascending k.
 #include "gemm_bf16.h"
 #include "route.h"
+#include "route_resident.h"
 
 namespace moe {
 
@@ -38,8 +39,8 @@ __global__ __launch_bounds__(256) void pack_matrix_kernel(const bf16_t *__restri
 }
 
 // MB row blocks of 32 tokens per workgroup: 1 for small batches (many small workgroups hide the
-// k-loop latency), 4 for large ones (every workgroup reads the whole packed router matrix from
-// L2, so fewer, taller tiles cut that traffic).
+// k-loop latency), 2 above 8192 tokens (every workgroup reads the whole packed router matrix from L2, so
+// taller tiles cut that traffic; the 256-expert shapes go to route_resident_kernel from 16384 tokens on).
 template <int NB, int MB>
 __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *__restrict__ x,
                                                                   const bf16_t *__restrict__ wr_packed,
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void route_mfma_kernel(const bf16_t *
     constexpr int E = NB * 128;
     constexpr int LDL = E + 8;                    // 8 threads per row, 4 rows per half wavefront: bank 8 r + sub
     constexpr int RT_BM = MB * 32;
-    constexpr int BK = MB == 4 ? 64 : RT_BK;      // keeps the staging buffers under 64 KB
+    constexpr int BK = RT_BK;
     constexpr int STAGE_BYTES = gemm_lds_elems<MB, BK>() * 2, TILE_BYTES = 32 * LDL * 4;
     // the logits tile reuses the A staging buffers, which are free once the product is done
     __shared__ __attribute__((aligned(16))) char smem[STAGE_BYTES > TILE_BYTES ? STAGE_BYTES : TILE_BYTES];
@@ -276,6 +277,36 @@ int route_launch(const void *x, const void *w_router, int w_layout, const float 
             if (rc != MOE_OK) return rc;
             wp = ws;
         }
+        // large batches of the 256-expert shapes: persistent workgroups with the router matrix in registers
+        if (E == RR_E && T >= RR_MIN_T && (d == 768 || d == 512 || d == 256)) {
+            int dev = 0, n_cu = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1) {
+                set_error("%s: cannot read the compute unit count", who);
+                return MOE_ERR_HIP;
+            }
+            const int n_tiles = ceil_div(T, RR_BM);
+            const int grid = n_tiles < n_cu ? n_tiles : n_cu;
+#define MOE_ROUTE_RESIDENT(KS_)                                                                                  \
+    if (top_k > 1)                                                                                               \
+        hipLaunchKernelGGL((route_resident_kernel<KS_, true>), dim3(grid), dim3(GEMM_THREADS), 0, st,            \
+                           (const bf16_t *)x, (const bf16_t *)wp, b_router, T, top_k, renormalize, idx, prob,    \
+                           logits_opt);                                                                          \
+    else                                                                                                         \
+        hipLaunchKernelGGL((route_resident_kernel<KS_, false>), dim3(grid), dim3(GEMM_THREADS), 0, st,           \
+                           (const bf16_t *)x, (const bf16_t *)wp, b_router, T, top_k, renormalize, idx, prob,    \
+                           logits_opt)
+            if (d == 768) {
+                MOE_ROUTE_RESIDENT(48);
+            } else if (d == 512) {
+                MOE_ROUTE_RESIDENT(32);
+            } else {
+                MOE_ROUTE_RESIDENT(16);
+            }
+#undef MOE_ROUTE_RESIDENT
+            MOE_CHECK_LAUNCH(who);
+            return MOE_OK;
+        }
         const int mbk = T <= 8192 ? 1 : 2;
         int grid = ceil_div(T, 32 * mbk);
 #define MOE_ROUTE_LAUNCH(NB_, MB_)                                                                            \
@@ -283,12 +314,10 @@ int route_launch(const void *x, const void *w_router, int w_layout, const float 
                        (const bf16_t *)wp, b_router, T, d, top_k, renormalize, idx, prob, logits_opt)
         if (E == 128) {
             if (mbk == 1) MOE_ROUTE_LAUNCH(1, 1);
-            else if (mbk == 2) MOE_ROUTE_LAUNCH(1, 2);
-            else MOE_ROUTE_LAUNCH(1, 4);
+            else MOE_ROUTE_LAUNCH(1, 2);
         } else {
             if (mbk == 1) MOE_ROUTE_LAUNCH(2, 1);
-            else if (mbk == 2) MOE_ROUTE_LAUNCH(2, 2);
-            else MOE_ROUTE_LAUNCH(2, 4);
+            else MOE_ROUTE_LAUNCH(2, 2);
         }
 #undef MOE_ROUTE_LAUNCH
     } else if (dtype == MOE_BF16) {

@@ -181,7 +181,10 @@ def test_route_config1_identical():
 
 
 @pytest.mark.parametrize("T,d,E,bias", [(4096, 768, 128, True), (1000, 768, 256, True), (333, 128, 128, False),
-                                        (500, 64, 24, True), (70, 256, 512, False)])
+                                        (500, 64, 24, True), (70, 256, 512, False),
+                                        # 256 experts from 16384 tokens on: persistent workgroups, router matrix in
+                                        # registers; more tiles than workgroups, a ragged last tile, every width built
+                                        (16384 + 21, 768, 256, True), (16385, 512, 256, False), (40000, 256, 256, True)])
 def test_route_bf16(T, d, E, bias):
     c = synth.moe_layer_inputs(T, d, 8, E, synth.BF16, 1.0, 900 + T, weights=False)
     b = c["b_router"] if bias else None

@@ -38,6 +38,8 @@ def _check_choices(g_idx, g_w, ref, tau, renormalize, what, wtol=1e-4):
 @pytest.mark.parametrize("T,d,E,dtype,k,renorm", [
     (1000, 128, 128, synth.BF16, 3, False),      # matrix-core router, ragged last tile
     (9000, 256, 256, synth.BF16, 2, True),       # its two-row-block build
+    (16384 + 45, 256, 256, synth.BF16, 3, True),  # persistent router with the matrix in registers, ragged last tile
+    (20000, 768, 256, synth.BF16, 2, False),     # the same at the benchmark's width
     (333, 128, 128, synth.BF16, 8, True),        # k at the limit
     (500, 64, 12, synth.F32, 3, False),          # generic router, fp32
     (257, 40, 70, synth.BF16, 5, True),          # generic router, E over one wavefront
