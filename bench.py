@@ -166,6 +166,9 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the measured ceilings (a 1 GiB read stream, plain and non-temporal, and a "
+                         "matrix-instruction loop with the dense tile's instruction mix)")
     ap.add_argument("--pmc-calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a reference dispatch of known size for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -325,14 +328,37 @@ def main():
     bytes_g2 = active * F * d * esz + K * F * esz + K * d * esz
     flops = 2.0 * K * d * F
     dom = ("ffn_gemm1", g1, bytes_g1) if g1 >= g2 else ("ffn_gemm2", g2, bytes_g2)
-    ach = dom[2] / (dom[1] * 1e-3) / 1e9
-    roofline = dict(bound="hbm", kernel=dom[0], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(ach / HBM_PEAK_GBS, 4),
-                    traffic=PMC_TRAFFIC_BYTES.get(a.workload, {}).get(dom[0]),
-                    avg_ms=round(dom[1], 5), algorithmic_bytes=int(dom[2]),
+    ach = dom[2] / (dom[1] * 1e-3) / 1e9                         # GB/s of algorithmic bytes
+    tfl = flops / (dom[1] * 1e-3) / 1e12                         # TFLOP/s of the same launch
+    # Which roof binds the dominant launch: the time its algorithmic bytes take at the HBM peak against the
+    # time its flops take at the matrix-core peak (fp32 workload 1: the vector fp32 peak stands in)
+    peak_tfl = MFMA_BF16_PEAK_TFLOPS if not fp32 else 157.3
+    t_hbm, t_mma = dom[2] / (HBM_PEAK_GBS * 1e9), flops / (peak_tfl * 1e12)
+    bound = "hbm" if t_hbm >= t_mma else ("mfma" if not fp32 else "alu")
+    traffic = PMC_TRAFFIC_BYTES.get(a.workload, {}).get(dom[0])
+    if bound == "hbm":
+        roofline = dict(bound="hbm", kernel=dom[0], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(ach / HBM_PEAK_GBS, 4))
+    else:
+        roofline = dict(bound=bound, kernel=dom[0], achieved=round(tfl, 1), peak=peak_tfl, unit="TFLOP/s",
+                        frac=round(tfl / peak_tfl, 4))
+    roofline.update(traffic=traffic,
+                    traffic_source=None if traffic is None else f"profiles/ (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of {dom[0]}, "
+                                                              "scaled by a 1 GiB copy; a constant refreshed with the kernels)",
+                    avg_ms=round(dom[1], 5), algorithmic_bytes=int(dom[2]), flops=int(flops),
+                    ideal_ms_at_hbm_peak=round(t_hbm * 1e3, 5), ideal_ms_at_matrix_peak=round(t_mma * 1e3, 5),
+                    hbm_frac_of_peak=round(ach / HBM_PEAK_GBS, 4),
                     ffn_gemm1_ms=round(g1, 5), ffn_gemm2_ms=round(g2, 5),
                     ffn_mfma_tflops=round(2 * flops / ((g1 + g2) * 1e-3) / 1e12, 2),
                     ffn_mfma_frac_of_bf16_peak=round(2 * flops / ((g1 + g2) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4))
+    if not a.no_ceilings:
+        # what this machine delivers to a kernel of the same shape: a pure read stream, a pure matrix-instruction loop
+        cl = moe.measure_ceilings()
+        roofline["measured_peak"] = cl
+        if bound == "hbm":
+            roofline["frac_of_measured_peak"] = round(ach / cl["hbm_read_nontemporal_GBs"], 4)
+        elif bound == "mfma":
+            roofline["frac_of_measured_peak"] = round(tfl / cl["mfma_bf16_operands_from_lds_TFLOPs"], 4)
 
     # the same step captured once into a HIP graph and replayed (the library allocates nothing, records no
     # memset and never synchronises, so the whole chain of launches is capturable)
@@ -377,6 +403,9 @@ def main():
             modes[name] = round(T / (ms * 1e-3), 1)
             extra_ms[name] = round(ms, 5)
     kept0 = int(layer0.disp_out["kept"].sum().item()) if "off_budget0" in modes else None
+    # tokens that actually went through an expert, per second: "on" and "off_same_plan" keep the same K rows,
+    # budget 0 keeps fewer (less work per input token)
+    kept_rate = {m: round((kept0 if m == "off_budget0" else K) / (extra_ms[m] * 1e-3), 1) for m in modes}
 
     if a.pmc_calibration_copy:
         src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
@@ -407,6 +436,7 @@ def main():
         "cpu_baseline": cpu,
         "replication_modes_tokens_per_s": modes,
         "replication_modes_ms": extra_ms,
+        "kept_tokens_per_s": kept_rate,
         "ms_per_step_with_kernel_events": round(ms_on_events, 5),
         # from the pass with events between the calls (they cost a few us per step)
         "ms_per_step_median_with_call_events": round(float(np.median(step_ms)), 5), "ms_per_step_min_with_call_events": round(float(np.min(step_ms)), 5),

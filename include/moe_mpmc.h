@@ -303,6 +303,27 @@ int moe_expert_ffn_timed(const void *x, int n_x_rows, const int32_t *row_index, 
                          int E, int d, int F, int dtype, int schedule, void *y_perm, void *ws,
                          size_t ws_bytes, void *stream, void *ev_before, void *ev_between, void *ev_after);
 
+
+/* Ceilings of this machine for kernels shaped like the library's own (the benchmark quotes roofline
+ * fractions against them beside the nominal peaks).
+ * moe_measure_stream_read: one launch that reads `bytes` (a multiple of 16) of device memory once, a
+ *   contiguous region per workgroup, with plain (nontemporal = 0) or non-temporal 16-byte loads, from
+ *   n_workgroups workgroups of 256 threads (0: eight per compute unit, the whole chip; 1: what a single
+ *   workgroup, hence a single compute unit, can pull from memory -- the rate that bounds a kernel which
+ *   gives every expert slot to one workgroup).
+ * moe_measure_mfma_bf16: one launch of `iters` iterations of 32 v_mfma_f32_32x32x16_bf16 per wavefront (one
+ *   workgroup of 4 wavefronts per compute unit, 4 x 4 accumulator blocks each, the 256 x 256 tile kernel's
+ *   instruction mix) on operands that change every step, kept in registers (from_lds = 0) or re-read from
+ *   LDS (from_lds = 1); moe_measure_mfma_bf16_flops gives the floating-point operations of such a launch.
+ * sink: device scratch of moe_measure_sink_bytes() bytes (nothing meaningful is written).  The caller times
+ * the launches (events on the stream).
+ */
+size_t moe_measure_sink_bytes(void);
+int moe_measure_stream_read(const void *buf, size_t bytes, int nontemporal, int n_workgroups, void *sink,
+                            void *stream);
+size_t moe_measure_mfma_bf16_flops(int iters);
+int moe_measure_mfma_bf16(int iters, int from_lds, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,7 @@ EXPORTS = (
     "moe_combine",
     "moe_route_topk", "moe_dispatch_topk", "moe_expert_ffn_rows", "moe_combine_topk",
     "moe_plan_dispatch_workspace_bytes", "moe_plan_dispatch",
+    "moe_measure_sink_bytes", "moe_measure_stream_read", "moe_measure_mfma_bf16_flops", "moe_measure_mfma_bf16",
 )
 
 
@@ -69,7 +70,7 @@ def lib():
         _lib.moe_last_error.restype = C.c_char_p
         for n in EXPORTS:
             f = getattr(_lib, n)
-            if n.endswith("_bytes"):
+            if n.endswith("_bytes") or n.endswith("_flops"):
                 f.restype = C.c_size_t
             elif n not in ("moe_last_error", "moe_build_id"):
                 f.restype = C.c_int
@@ -93,6 +94,10 @@ def lib():
         _lib.moe_dispatch_topk.argtypes = [P, P, P, I, I, I, I, I, I, I, P, P, P, P, P, P, P, P, P, S, P]
         _lib.moe_expert_ffn_rows.argtypes = [P, I, P, P, P, I, P, P, P, I, I, I, I, I, I, I, P, P, S, P]
         _lib.moe_combine_topk.argtypes = [P, P, P, P, I, I, I, I, I, P, P]
+        _lib.moe_measure_sink_bytes.argtypes = []
+        _lib.moe_measure_stream_read.argtypes = [P, S, I, I, P, P]
+        _lib.moe_measure_mfma_bf16_flops.argtypes = [I]
+        _lib.moe_measure_mfma_bf16.argtypes = [I, I, P, P]
         _lib.moe_plan_dispatch_workspace_bytes.argtypes = [I, I, I, I]
         _lib.moe_plan_dispatch.argtypes = [P, I, P, I, I, I, I, I, I] + [P] * 12 + [P, S, P]
     return _lib
@@ -313,6 +318,41 @@ def moe_plan_dispatch(plan_idx, expert_idx, E, budget, slot_capacity, policy=0, 
                                    _ptr(do["inv"]), _ptr(do.get("row_token")), _ptr(ws),
                                    ws.numel() if ws is not None else 0, _stream()))
     return po, do
+
+
+# --------------------------------------------------------------------------- measurement
+def measure_ceilings(read_bytes=1 << 30, mfma_iters=4000, repeats=5):
+    """Event-timed ceilings of this machine for kernels shaped like the library's (see the header's
+    measurement section): best of ``repeats`` launches each.  -> dict of GB/s and TFLOP/s."""
+    dev = torch.device("cuda")
+    L = lib()
+    sink = torch.zeros(L.moe_measure_sink_bytes(), dtype=torch.uint8, device=dev)
+    buf = torch.empty(read_bytes, dtype=torch.uint8, device=dev)
+    buf.random_(0, 255)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+
+    def best(launch):
+        t = []
+        for _ in range(repeats + 1):
+            ev[0].record()
+            _check(launch())
+            ev[1].record()
+            torch.cuda.synchronize()
+            t.append(ev[0].elapsed_time(ev[1]))
+        return min(t[1:]) * 1e-3
+
+    st = _stream()
+    out = {}
+    for nt, name in ((0, "hbm_read_GBs"), (1, "hbm_read_nontemporal_GBs")):
+        out[name] = round(read_bytes / best(lambda: L.moe_measure_stream_read(_ptr(buf), read_bytes, nt, 0, _ptr(sink), st)) / 1e9, 1)
+    # one workgroup alone (one compute unit), 64 MiB: the per-CU stream rate
+    one = 1 << 26
+    for wgs, name in ((1, "one_workgroup_read_GBs"), (2, "two_workgroups_read_GBs")):
+        out[name] = round(one / best(lambda: L.moe_measure_stream_read(_ptr(buf), one, 1, wgs, _ptr(sink), st)) / 1e9, 1)
+    flops = L.moe_measure_mfma_bf16_flops(mfma_iters)
+    for fl, name in ((0, "mfma_bf16_registers_TFLOPs"), (1, "mfma_bf16_operands_from_lds_TFLOPs")):
+        out[name] = round(flops / best(lambda: L.moe_measure_mfma_bf16(mfma_iters, fl, _ptr(sink), st)) / 1e12, 1)
+    return out
 
 
 # --------------------------------------------------------------------------- top-k routing

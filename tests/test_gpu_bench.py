@@ -40,5 +40,11 @@ def test_bench_line_has_the_contract_fields():
     rt = j["config"]["routing"]
     assert rt["assignments"] == j["config"]["T"] and 0 < rt["max_expert_share"] <= 1
     assert rt["replicas_granted"] <= min(rt["replicas_wanted"], j["config"]["replica_budget"])
+    mp = rf["measured_peak"]
+    assert 2000 < mp["hbm_read_GBs"] < 8000 and 2000 < mp["hbm_read_nontemporal_GBs"] < 8000
+    assert 300 < mp["mfma_bf16_operands_from_lds_TFLOPs"] < 2600 and 300 < mp["mfma_bf16_registers_TFLOPs"] < 2600
+    assert 5 < mp["one_workgroup_read_GBs"] < 500
+    assert abs(rf["frac_of_measured_peak"] - rf["achieved"] / mp["hbm_read_nontemporal_GBs"]) < 1e-3
+    assert set(j["kept_tokens_per_s"]) == set(m)
     pc = j["per_call_ms_median"]
     assert set(pc) == {"moe_route", "moe_plan_dispatch", "moe_expert_ffn", "moe_combine"} and all(v > 0 for v in pc.values())
