@@ -27,15 +27,23 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
-# HBM bytes per launch (fetched + written) of the two FFN GEMM kernels, from two rocprofv3 --pmc
-# runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads
-# for a plain 1 GiB copy (fetch x1.9999, write x1.0000); figures and commands in
-# profiles/moe_layer_cfg2.md (and _cfg4, _cfg5).  Counters cannot be read inside a normal run, so the value is
-# carried here and refreshed whenever those kernels change.
-PMC_TRAFFIC_BYTES = {"cfg2": {"ffn_gemm1": 631.31e6 + 15.12e6, "ffn_gemm2": 621.04e6 + 3.78e6},
-                     "cfg4": {"ffn_gemm1": 1252.55e6 + 40.63e6, "ffn_gemm2": 1231.44e6 + 10.16e6},
-                     # cfg5: every row goes through the 256 x 256 tile kernel
-                     "cfg5": {"ffn_gemm1": 2060.13e6 + 402.65e6, "ffn_gemm2": 2236.10e6 + 100.66e6}}
+# HBM bytes per launch (fetched + written) of the two FFN product kernels, from two rocprofv3 --pmc
+# runs of this script per workload (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads
+# for a plain 1 GiB copy (fetch x1.9999, write x1.0000); figures and commands in profiles/ (moe_layer_*.md,
+# sru*_cfg3*.md).  Counters cannot be read inside a normal run, so the values are carried here and are
+# refreshed, with those files, whenever these kernels change (roofline.traffic_source says so in the line).
+PMC_TRAFFIC_BYTES = {
+    "cfg1": {"ffn_gemm1": 1.26e6 + 0.52e6, "ffn_gemm2": 1.31e6 + 0.13e6},
+    "cfg2": {"ffn_gemm1": 630.64e6 + 15.12e6, "ffn_gemm2": 621.2e6 + 3.78e6},
+    "cfg2k3": {"ffn_gemm1": 696.75e6 + 52.2e6, "ffn_gemm2": 744.72e6 + 13.05e6},
+    "cfg3": {"ffn_gemm1": 639.85e6 + 24.1e6, "ffn_gemm2": 638.42e6 + 6.02e6},
+    "cfg3x": {"ffn_gemm1": 637.33e6 + 23.25e6, "ffn_gemm2": 647.98e6 + 5.81e6},
+    "cfg4": {"ffn_gemm1": 1253.57e6 + 40.63e6, "ffn_gemm2": 1231.16e6 + 10.16e6},
+    "cfg4b": {"ffn_gemm1": 1243.98e6 + 63.36e6, "ffn_gemm2": 1267.19e6 + 15.84e6},
+    # cfg5: every row goes through the 256 x 256 tile kernel; cfg5stack runs six such layers per step
+    "cfg5": {"ffn_gemm1": 2073.13e6 + 402.65e6, "ffn_gemm2": 2236.88e6 + 100.66e6},
+    "cfg5stack": {"ffn_gemm1": 2073.13e6 + 402.65e6, "ffn_gemm2": 2236.88e6 + 100.66e6},
+}
 
 
 def _to_dev(a):
@@ -158,6 +166,62 @@ def _cpu_baseline(c, C, R, budget_s=20.0, serial_leg=True):
     return res
 
 
+def _ffn_split(moe, x, w1, w2, T, d, F, E, R, C, counts):
+    """moe_expert_ffn alone on slot tables made from this batch's expert loads: the busiest expert's rows only
+    (cut into slots of C rows), all other experts only, both, and as many rows spread evenly over all experts.
+    Event-timed per product.  Input construction only; every product runs in the library."""
+    import torch
+    hot = int(np.argmax(counts))
+
+    def slots_of(expert_rows):
+        rows, experts = [], []
+        for e, n in expert_rows:
+            n = int(min(n, T))
+            r = max(1, -(-n // C))
+            q, rem = divmod(n, r)
+            for k in range(r):
+                rows.append(q + (k < rem))
+                experts.append(e)
+        return rows, experts
+
+    cases = {
+        "hot_expert_only": slots_of([(hot, counts[hot])]),
+        "other_experts_only": slots_of([(e, counts[e]) for e in range(E) if e != hot]),
+        "both": slots_of([(e, counts[e]) for e in range(E)]),
+        "uniform_256_rows_per_expert": ([min(256, T // E)] * E, list(range(E))),
+        "uniform_64_rows_per_expert": ([min(64, T // E)] * E, list(range(E))),
+    }
+    out = {}
+    for name, (rows, experts) in cases.items():
+        P = len(rows)
+        max_slots = max(P, E + R)
+        so = np.zeros(max_slots + 1, np.int32)
+        so[1:P + 1] = np.cumsum(rows)
+        so[P + 1:] = so[P]
+        se = np.full(max_slots, -1, np.int32)
+        se[:P] = experts
+        so_t, se_t = torch.from_numpy(so).cuda(), torch.from_numpy(se).cuda()
+        ns = torch.tensor([P], dtype=torch.int32, device="cuda")
+        y = torch.empty_like(x)
+        ws = torch.empty(moe.lib().moe_expert_ffn_workspace_bytes(T, max_slots, d, F, moe.MOE_BF16), dtype=torch.uint8,
+                         device="cuda")
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(10)]
+        for t in evs:
+            for e in t:
+                e.record()
+        for i in range(10):
+            moe.moe_expert_ffn(x, w1, w2, so_t, se_t, ns, E, F, max_slots=max_slots, out=y, ws=ws, events=evs[i])
+        torch.cuda.synchronize()
+        g1 = float(np.mean([t[0].elapsed_time(t[1]) for t in evs[2:]]))
+        g2 = float(np.mean([t[1].elapsed_time(t[2]) for t in evs[2:]]))
+        K = int(so[P])
+        active = len(set(experts))
+        out[name] = {"rows": K, "slots": P, "experts": active, "ffn_gemm1_ms": round(g1, 5), "ffn_gemm2_ms": round(g2, 5),
+                     "gemm1_tflops": round(2.0 * K * d * F / g1 / 1e9, 1),
+                     "gemm1_algorithmic_GBs": round((active * d * F * 2 + K * d * 2 + K * F * 2) / g1 / 1e6, 1)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -172,6 +236,13 @@ def main():
     ap.add_argument("--pmc-calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a reference dispatch of known size for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--materialize-gather", action="store_true",
+                    help="top-1 workloads: moe_dispatch copies the kept rows into x_perm (dispatch_gather_kernel) and "
+                         "the first product reads that copy, instead of gathering through the permutation")
+    ap.add_argument("--ffn-split", action="store_true",
+                    help="also time moe_expert_ffn alone on synthetic slot tables cut from this workload's shape: the "
+                         "hot expert's slots only, the other experts only, both, and uniform slots (where the two "
+                         "products' time goes when matrix-bound and weight-streaming tiles share a launch)")
     ap.add_argument("--modes", default="on,off_same_plan,off_budget0",
                     help="replication modes to time besides 'on' (comma list)")
     a = ap.parse_args()
@@ -228,7 +299,12 @@ def main():
     # a stack hands the output of one layer to the next: two buffers in turn
     outs = [torch.empty(T, d, dtype=dt, device="cuda") for _ in range(2)] if n_layers > 1 else None
 
+    if a.materialize_gather and c.get("top_k", 1) != 1:
+        raise SystemExit("--materialize-gather is for the top-1 workloads")
+
     def chain(lay, schedule, marks=None, **kw):
+        if a.materialize_gather:
+            kw["fuse_gather"] = False
         cur = x
         for l, (wr_l, b_l, w1_l, w2_l) in enumerate(W):
             ffn_events = kw.pop("ffn_events", None) if l == 0 else None     # first layer of a stack only
@@ -415,6 +491,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    ffn_split = None
+    if a.ffn_split and not fp32 and top_k == 1:
+        ffn_split = _ffn_split(moe, x, w1, w2, T, d, F, E, R, C, counts)
+
     cpu = None
     if not a.no_cpu_baseline and sru is None:
         cpu = _cpu_baseline(c, C, R)
@@ -431,6 +511,7 @@ def main():
         "config": {"workload": desc, "name": a.workload, "T": T, "d_model": d, "d_ff": F, "experts": E,
                    "top_k": top_k, "slot_capacity": C, "replica_budget": R, "kept_tokens": K, "active_experts": active,
                    "slots": n_slots, "replication": "on (slot schedule)", "residual": RES, "layers_per_step": n_layers,
+                   "gather": "materialized by moe_dispatch" if a.materialize_gather else "fused into the first product",
                    "routing": routing},
         "roofline": roofline,
         "cpu_baseline": cpu,
@@ -446,6 +527,8 @@ def main():
     }
     if pipeline is not None:
         line["two_stream_pipeline"] = pipeline
+    if ffn_split is not None:
+        line["ffn_split"] = ffn_split
     print(json.dumps(line))
 
 
