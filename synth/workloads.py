@@ -108,9 +108,11 @@ def moe_layer_inputs(T: int, d: int, F: int, E: int, dtype: int, zipf_s: float, 
 
     x ~ N(0,1); Wr, W1, W2 ~ N(0, 0.02^2).  Popularity rank k (1 = hottest) is mapped to an
     expert id by a seeded permutation, and expert e gets the logit bias
-    ``kappa * ln(w_rank(e) / w_1)`` with ``kappa = sqrt(6)/pi * 0.02*sqrt(d)``: the Gaussian
-    spread of one logit then plays the role of Gumbel noise, so the share of tokens whose
-    largest logit is e comes out close to the Zipf share.
+    ``kappa * ln(w_rank(e) / w_1)`` with ``kappa = 0.5 * 0.02*sqrt(d)``: the Gaussian spread of
+    one logit (standard deviation 0.02*sqrt(d)) plays the role of Gumbel noise, so the share of
+    tokens whose largest logit is e comes out close to the Zipf share.  (The Gumbel-equivalent
+    factor sqrt(6)/pi = 0.78 over-concentrates, a Gaussian tail being lighter; 0.5 was calibrated by
+    simulation: the hottest expert's share lands within ~2 points of its Zipf share at E = 128/256.)
     """
     out = dict(T=T, d=d, F=F, E=E, dtype=dtype, seed=seed)
     out["x"] = normal_tensor((T, d), 1.0, [seed, 1], dtype)
