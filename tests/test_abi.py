@@ -120,6 +120,48 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.sru_predict(p, C.byref(wa), 8, 512, 1, p, None, p, 1 << 30, None) == INV
 
 
+def test_new_entry_points_reject_bad_arguments_on_the_host():
+    L = moe.lib()
+    buf = (C.c_char * 4096)()
+    p = C.cast(buf, C.c_void_p)
+    INV, UNS = -1, -2
+    # moe_dispatch_static: the checks of moe_dispatch, and its own size limit (refused before any device call)
+    ds = L.moe_dispatch_static
+    assert ds(p, p, None, 4, 64, 8, 0, 8, 0, p, p, p, p, p, p, p, None) == INV            # C = 0
+    assert ds(p, p, None, 4, 6, 8, 1, 8, 0, p, p, p, p, p, p, p, None) == INV             # row bytes
+    assert ds(p, p, None, 4, 64, 8, 1, 4, 0, p, p, p, p, p, p, p, None) == INV            # max_slots < E
+    assert ds(p, p, None, 300000, 64, 1024, 1, 1024, 0, p, p, p, p, p, p, p, None) == UNS  # 293 blocks x 1024 experts
+    assert b"static scratch" in L.moe_last_error()
+    # moe_expert_ffn_timed: same validation as the untimed calls
+    ft = L.moe_expert_ffn_timed
+    assert ft(p, 4, None, p, p, 0, p, p, p, 12, 8, 8, 64, 256, 0, 0, p, p, 1 << 30, None, None, None, None) == INV  # n_x_rows != max_rows
+    assert ft(p, 4, None, p, p, 0, p, p, p, 4, 8, 8, 64, 256, 0, 5, p, p, 1 << 30, None, None, None, None) == INV   # schedule
+    assert ft(p, 4, None, p, p, 0, p, p, p, 4, 8, 8, 768, 3072, 1, 0, p, p, 1 << 30, None, None, None, None) == UNS  # plain bf16
+    # measurement calls
+    assert L.moe_measure_stream_read(None, 1 << 20, 0, 0, p, None) == INV
+    assert L.moe_measure_stream_read(p, 100, 0, 0, p, None) == INV                        # not a multiple of 16
+    assert L.moe_measure_stream_read(p, 1 << 20, 2, 0, p, None) == INV                    # flag
+    assert L.moe_measure_mfma_bf16(0, 0, p, None) == INV
+    assert L.moe_measure_mfma_bf16(10, 2, p, None) == INV
+    assert L.moe_measure_mfma_bf16_flops(0) == 0
+    assert L.moe_build_id() is not None
+
+
+def test_a_library_built_from_other_sources_is_refused(monkeypatch):
+    """binding.lib() compares the source hash compiled into the library with the sources beside it."""
+    from paper_2605_11537_amd import binding, build
+    L = moe.lib()
+    L.moe_build_id.restype = C.c_char_p
+    assert L.moe_build_id().decode() == build.source_id()
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(build, "source_id", lambda: "0123456789abcdef")
+    with pytest.raises(RuntimeError) as ei:
+        binding.lib()
+    assert "rebuild" in str(ei.value)
+    monkeypatch.undo()
+    assert binding.lib() is not None
+
+
 def test_bench_refuses_more_than_one_gpu():
     """One GPU per box: the bench says so and exits before touching any device."""
     import subprocess

@@ -322,6 +322,27 @@ def test_ffn_first_product_h(case):
     assert_close(to_host(y)[:K], ref_y[:K], synth.BF16, "y")
 
 
+def test_ffn_timed_call_equals_untimed_and_records_its_events():
+    """moe_expert_ffn_timed (measurement section of the header): same bits as moe_expert_ffn, three events
+    recorded in order around the two products."""
+    E, d, F = 4, 128, 256
+    rows, experts = [70, 3, 0, 129, 64], [0, 1, 1, 2, 3]
+    so, se = _slots_for(rows, experts)
+    T = int(so[-1])
+    x = to_dev(synth.normal_tensor((T, d), 1.0, [61], synth.BF16))
+    w1 = moe.moe_pack_weights(to_dev(synth.normal_tensor((E, d, F), 0.05, [62], synth.BF16)))
+    w2 = moe.moe_pack_weights(to_dev(synth.normal_tensor((E, F, d), 0.05, [63], synth.BF16)))
+    args = (w1, w2, to_dev(so), to_dev(se), torch.tensor([len(rows)], dtype=torch.int32, device="cuda"), E, F)
+    y = moe.moe_expert_ffn(x, *args)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for e in evs:
+        e.record()
+    y_t = moe.moe_expert_ffn(x, *args, events=evs)
+    _sync()
+    assert torch.equal(y, y_t)
+    assert evs[0].elapsed_time(evs[1]) > 0 and evs[1].elapsed_time(evs[2]) > 0
+
+
 def test_ffn_bf16_dense_tiles():
     """Enough rows that the 256 x 256 tile kernel takes the slots: lengths around its cut points
     (pieces of 1..256 rows use 1..8 row blocks of the tile), short and empty slots beside them, and
