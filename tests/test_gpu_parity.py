@@ -377,6 +377,87 @@ def test_ffn_bf16_dense_tiles():
     assert torch.equal(y, y3) or torch.equal(y[:K], y3[:K])
 
 
+def test_ffn_bf16_many_short_slots_beside_long_ones():
+    """The tile kernel on matrices other than the small test's (d = 512, F = 768: two and three column tiles,
+    16 and 24 k stages): rests of 1..128 rows with 1..4 row blocks beside full 256-row ranges and rests above
+    128 rows, 32 single-slot experts of 1..128 rows (tiles that only stream their weights), an expert with two
+    short slots (shared weights), empty slots, the fused gather.  Every element of h and of the output against
+    the oracle, and bit for bit against the experts schedule, which runs the 128-column kernel alone and
+    accumulates in the same order."""
+    E, d, F = 40, 512, 768
+    rng = np.random.default_rng(7)
+    rows = [1500, 129, 0, 256, 257, 1, 385, 2000, 128, 513, 384, 64, 65, 96, 289, 320, 321, 32, 160, 224, 97, 127, 33]
+    experts = [0, 0, 1, 1, 2, 2, 3, 3, 3, 4, 4, 4, 5, 5, 5, 5, 6, 6, 6, 6, 6, 7, 7]
+    for e in range(8, E):                         # many single-slot experts with short rows
+        rows.append(int(rng.integers(1, 129)))
+        experts.append(e)
+    so, se = _slots_for(rows, experts)
+    K = int(so[-1])
+    T = K + 5
+    assert T >= 4096 and T >= 64 * len(rows)        # the sizes at which the library uses the tile kernels
+    x = synth.normal_tensor((T, d), 1.0, [71], synth.BF16)
+    w1 = synth.normal_tensor((E, d, F), 0.05, [72], synth.BF16)
+    w2 = synth.normal_tensor((E, F, d), 0.05, [73], synth.BF16)
+    ref_y, ref_h = oracle.ffn(x, w1, w2, so, se, len(rows), want_h=True)
+    args = (moe.moe_pack_weights(to_dev(w1)), moe.moe_pack_weights(to_dev(w2)), to_dev(so), to_dev(se),
+            torch.tensor([len(rows)], dtype=torch.int32, device="cuda"), E, F)
+    ws = torch.zeros(moe.lib().moe_expert_ffn_workspace_bytes(T, len(rows), d, F, moe.MOE_BF16), dtype=torch.uint8,
+                     device="cuda")
+    y = moe.moe_expert_ffn(to_dev(x), *args, ws=ws)
+    _sync()
+    h = to_host(ws[:T * F * 2].view(torch.bfloat16).view(T, F))
+    assert_close(h[:K], ref_h[:K], synth.BF16, "h, many short slots")
+    assert (h[K:] == 0).all()                       # rows outside all slots are not written
+    assert_close(to_host(y)[:K], ref_y[:K], synth.BF16, "ffn bf16, many short slots")
+    g, r = f64(to_host(y)[:K]), f64(ref_y[:K])
+    assert (np.abs(g - r) <= 2.0 ** -7 * np.abs(r) + 1e-3 * np.abs(r).max()).all()
+    y_off = moe.moe_expert_ffn(to_dev(x), *args, schedule=1)
+    assert torch.equal(y[:K], y_off[:K])
+    perm = np.random.default_rng(2).permutation(T).astype(np.int32)
+    x_src = np.zeros_like(x)
+    x_src[perm] = x
+    y2 = moe.moe_expert_ffn(to_dev(x_src), *args, row_index=to_dev(perm))
+    assert torch.equal(y[:K], y2[:K])
+    y3 = moe.moe_expert_ffn(to_dev(x), *args)           # twice in a row: nothing stale in the work lists
+    assert torch.equal(y[:K], y3[:K])
+
+
+def test_ffn_bf16_short_tiles_several_per_workgroup():
+    """More short row ranges x column tiles than the chip has compute units: every persistent workgroup of the
+    tile kernel walks several tiles of at most 128 rows (loads of the next tile's first stages and its row
+    numbers issued during the current one, epilogue stores in flight while the next tile starts), at the
+    d = 768 of the workloads.  128 experts of 64..128 rows, some with a second slot; with and without the gather."""
+    E, d, F = 128, 768, 1536
+    rng = np.random.default_rng(11)
+    rows, experts = [], []
+    for e in range(E):
+        rows.append(int(rng.integers(64, 129)))
+        experts.append(e)
+        if e % 17 == 3:
+            rows.append(int(rng.integers(64, 129)))
+            experts.append(e)
+    so, se = _slots_for(rows, experts)
+    K = int(so[-1])
+    T = K + 2
+    assert T >= 4096 and T >= 64 * len(rows) and len(rows) * (F // 256) > 3 * 256
+    x = synth.normal_tensor((T, d), 1.0, [81], synth.BF16)
+    w1 = synth.normal_tensor((E, d, F), 0.05, [82], synth.BF16)
+    w2 = synth.normal_tensor((E, F, d), 0.05, [83], synth.BF16)
+    ref = oracle.ffn(x, w1, w2, so, se, len(rows))
+    args = (moe.moe_pack_weights(to_dev(w1)), moe.moe_pack_weights(to_dev(w2)), to_dev(so), to_dev(se),
+            torch.tensor([len(rows)], dtype=torch.int32, device="cuda"), E, F)
+    y = moe.moe_expert_ffn(to_dev(x), *args)
+    _sync()
+    assert_close(to_host(y)[:K], ref[:K], synth.BF16, "ffn bf16 short tiles, several per workgroup")
+    y_off = moe.moe_expert_ffn(to_dev(x), *args, schedule=1)
+    assert torch.equal(y[:K], y_off[:K])
+    perm = np.random.default_rng(12).permutation(T).astype(np.int32)
+    x_src = np.zeros_like(x)
+    x_src[perm] = x
+    y2 = moe.moe_expert_ffn(to_dev(x_src), *args, row_index=to_dev(perm))
+    assert torch.equal(y[:K], y2[:K])
+
+
 def test_ffn_bf16_dense_tiles_persistent():
     """More 256-row tiles than the chip has compute units, so the persistent workgroups of the tile
     kernel walk several tiles each (prefetch across tiles, epilogue stores still in flight).  The
