@@ -308,9 +308,9 @@ int moe_expert_ffn_timed(const void *x, int n_x_rows, const int32_t *row_index, 
  * fractions against them beside the nominal peaks).
  * moe_measure_stream_read: one launch that reads `bytes` (a multiple of 16) of device memory once, a
  *   contiguous region per workgroup, with plain (nontemporal = 0) or non-temporal 16-byte loads, from
- *   n_workgroups workgroups of 256 threads (0: eight per compute unit, the whole chip; 1: what a single
- *   workgroup, hence a single compute unit, can pull from memory -- the rate that bounds a kernel which
- *   gives every expert slot to one workgroup).
+ *   n_workgroups workgroups of 256 threads (0: eight per compute unit, 16 KB in flight each: the whole chip;
+ *   1 .. number of compute units: one workgroup per unit, 128 KB in flight each: what that many units can
+ *   pull from memory -- the rate that bounds a kernel which gives every expert slot to one workgroup).
  * moe_measure_mfma_bf16: one launch of `iters` iterations of 32 v_mfma_f32_32x32x16_bf16 per wavefront (one
  *   workgroup of 4 wavefronts per compute unit, 4 x 4 accumulator blocks each, the 256 x 256 tile kernel's
  *   instruction mix) on operands that change every step, kept in registers (from_lds = 0) or re-read from

@@ -345,10 +345,11 @@ def measure_ceilings(read_bytes=1 << 30, mfma_iters=4000, repeats=5):
     out = {}
     for nt, name in ((0, "hbm_read_GBs"), (1, "hbm_read_nontemporal_GBs")):
         out[name] = round(read_bytes / best(lambda: L.moe_measure_stream_read(_ptr(buf), read_bytes, nt, 0, _ptr(sink), st)) / 1e9, 1)
-    # one workgroup alone (one compute unit), 64 MiB: the per-CU stream rate
-    one = 1 << 26
-    for wgs, name in ((1, "one_workgroup_read_GBs"), (2, "two_workgroups_read_GBs")):
-        out[name] = round(one / best(lambda: L.moe_measure_stream_read(_ptr(buf), one, 1, wgs, _ptr(sink), st)) / 1e9, 1)
+    # one workgroup per compute unit on 1, 2, 144 units (128 KB in flight each): the per-CU stream rate, and
+    # what a kernel with one workgroup per expert slot of the 144-slot workload could pull
+    for wgs, name, nbytes in ((1, "one_workgroup_read_GBs", 1 << 26), (2, "two_workgroups_read_GBs", 1 << 26),
+                              (144, "workgroups_144_read_GBs", read_bytes)):
+        out[name] = round(nbytes / best(lambda: L.moe_measure_stream_read(_ptr(buf), nbytes, 1, wgs, _ptr(sink), st)) / 1e9, 1)
     flops = L.moe_measure_mfma_bf16_flops(mfma_iters)
     for fl, name in ((0, "mfma_bf16_registers_TFLOPs"), (1, "mfma_bf16_operands_from_lds_TFLOPs")):
         out[name] = round(flops / best(lambda: L.moe_measure_mfma_bf16(mfma_iters, fl, _ptr(sink), st)) / 1e12, 1)

@@ -4,7 +4,8 @@
 //
 //   moe_measure_stream_read   every workgroup streams its share of a buffer with 16-byte loads (plain or
 //                             non-temporal), as the weight-streaming GEMM tiles do; nothing is stored
-//                             but one word per workgroup
+//                             but one word per workgroup.  With one workgroup per compute unit or fewer,
+//                             each keeps 128 KB in flight (the rate of a unit's load path)
 //   moe_measure_mfma_bf16     one workgroup of 4 wavefronts per CU, each wavefront 4 x 4 accumulator blocks
 //                             (256 registers) of v_mfma_f32_32x32x16_bf16 -- the instruction mix of the
 //                             256 x 256 tile kernel -- with operands that change every step, either held in
@@ -16,21 +17,21 @@ namespace moe {
 
 typedef unsigned meas_u32x4_t __attribute__((ext_vector_type(4)));
 
-template <bool NT>
+template <bool NT, int U>
 __global__ __launch_bounds__(256) void measure_stream_read_kernel(const meas_u32x4_t *__restrict__ buf, size_t n_vec,
                                                                   unsigned *__restrict__ sink)
 {
-    // contiguous region per workgroup, walked front to back 4 KB (256 lanes x 16 bytes) at a time, 4 loads in flight
+    // contiguous region per workgroup, walked front to back U x 4 KB (256 lanes x 16 bytes) at a time, U loads in flight
     const size_t per = (n_vec + gridDim.x - 1) / gridDim.x;
     const size_t begin = per * blockIdx.x, end = begin + per < n_vec ? begin + per : n_vec;
     meas_u32x4_t acc = {0u, 0u, 0u, 0u};
     size_t i = begin + threadIdx.x;
-    for (; i + 768 < end; i += 1024) {
-        meas_u32x4_t v[4];
+    for (; i + 256 * (U - 1) < end; i += 256 * U) {
+        meas_u32x4_t v[U];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = NT ? __builtin_nontemporal_load(buf + i + 256 * u) : buf[i + 256 * u];
+        for (int u = 0; u < U; ++u) v[u] = NT ? __builtin_nontemporal_load(buf + i + 256 * u) : buf[i + 256 * u];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc ^= v[u];
+        for (int u = 0; u < U; ++u) acc ^= v[u];
     }
     for (; i < end; i += 256) acc ^= NT ? __builtin_nontemporal_load(buf + i) : buf[i];
     const unsigned r = acc.x ^ acc.y ^ acc.z ^ acc.w;
@@ -118,12 +119,13 @@ extern "C" int moe_measure_stream_read(const void *buf, size_t bytes, int nontem
     MOE_REQUIRE(n_workgroups >= 0 && n_workgroups <= n_cu * 8, MOE_ERR_INVALID_ARG,
                 "moe_measure_stream_read: n_workgroups=%d outside 0..%d", n_workgroups, n_cu * 8);
     const int grid = n_workgroups > 0 ? n_workgroups : n_cu * 8;      // sink holds a word per workgroup
-    if (nontemporal)
-        hipLaunchKernelGGL(measure_stream_read_kernel<true>, dim3(grid), dim3(256), 0, (hipStream_t)stream,
-                           (const meas_u32x4_t *)buf, bytes / 16, (unsigned *)sink);
-    else
-        hipLaunchKernelGGL(measure_stream_read_kernel<false>, dim3(grid), dim3(256), 0, (hipStream_t)stream,
-                           (const meas_u32x4_t *)buf, bytes / 16, (unsigned *)sink);
+    // one workgroup per compute unit at most: 32 loads (128 KB per workgroup) in flight, so that the rate shown is
+    // what the unit's load path gives and not what 16 KB in flight wait for; the whole chip: 4 loads, 8 workgroups per unit
+    const bool deep = n_workgroups > 0 && n_workgroups <= n_cu;
+    auto kern = deep ? (nontemporal ? measure_stream_read_kernel<true, 32> : measure_stream_read_kernel<false, 32>)
+                     : (nontemporal ? measure_stream_read_kernel<true, 4> : measure_stream_read_kernel<false, 4>);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const meas_u32x4_t *)buf, bytes / 16,
+                       (unsigned *)sink);
     MOE_CHECK_LAUNCH("moe_measure_stream_read");
     return MOE_OK;
 }
