@@ -103,7 +103,8 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
     // ---- tables.  Pass 1: thread per expert (strided), coalesced over the block histograms.
     for (int e = tid; e < E; e += DSP_THREADS) {
         int tot = 0, bef = 0;
-#pragma unroll 8
+        // 16 loads in flight per thread: at 64 blocks this loop is four memory round trips instead of eight
+#pragma unroll 16
         for (int b = 0; b < nb; ++b) {
             int v = block_hist[(size_t)b * E + e];
             bef += b < (int)blockIdx.x ? v : 0;
@@ -125,12 +126,44 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
             cap_e[e] = (long long)tot < cap ? tot : (int)cap;
         }
     }
+    // ---- ranks inside the block.  With the plan made in here, wavefront 0 is busy with the allocation (a
+    // dependent chain of microseconds) and the other three rank all 16 chunks meanwhile; otherwise all four
+    // wavefronts take four chunks each.
+    constexpr int RANK_WAVES = PPL > 0 ? DSP_THREADS / WAVE - 1 : DSP_THREADS / WAVE;
+    constexpr int RANK_ROUNDS = (DSP_CHUNKS + RANK_WAVES - 1) / RANK_WAVES;
+    const int rank_w = PPL > 0 ? w - 1 : w;          // -1: this wavefront ranks nothing
+    int my_e[RANK_ROUNDS], my_rank[RANK_ROUNDS];
+    auto rank_chunks = [&]() {
+#pragma unroll
+        for (int rd = 0; rd < RANK_ROUNDS; ++rd) {
+            const int c = rd * RANK_WAVES + rank_w;
+            my_e[rd] = -1;
+            my_rank[rd] = 0;
+            if (c >= DSP_CHUNKS) continue;            // uniform per wavefront
+            int t = base + c * WAVE + lane;
+            bool valid = t < T;
+            int e = valid ? idx[t] : 0;
+            valid = valid && e >= 0 && e < E;
+            unsigned long long mask = __ballot(valid);
+            for (int b = 0; b < nbits; ++b) {
+                bool bit = (e >> b) & 1;
+                unsigned long long bal = __ballot(bit);
+                mask &= bit ? bal : ~bal;
+            }
+            int rank = __popcll(mask & ((1ull << lane) - 1ull));
+            if (valid && rank == 0) chunk_cnt[c][e] = (unsigned short)__popcll(mask);
+            my_e[rd] = valid ? e : -1;
+            my_rank[rd] = rank;
+        }
+    };
     if (PPL > 0) {
         for (int e = E + tid; e < MOE_MAX_EXPERTS; e += DSP_THREADS) plan_hist[e] = 0;
-        __syncthreads();
+        __syncthreads();                  // the chunk table is clear, the plan's histogram complete
         if (tid < WAVE)
             plan_allocate_wave<(PPL > 0 ? PPL : 1)>(plan_hist, rep, pa.n_plan_ids, E, pa.R, C, pa.policy, pa.replicas,
                                                     pa.plan_counts, blockIdx.x == 0);
+        else
+            rank_chunks();
         __syncthreads();
         for (int e = tid; e < E; e += DSP_THREADS) {
             const long long cap = (long long)rep[e] * C;
@@ -192,29 +225,9 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
                 for (int p = P + tid; p < E + pa.R; p += DSP_THREADS) pa.slot_expert[p] = -1;
         }
     }
-    __syncthreads();
     if (T == 0) return;
 
-    // ---- ranks inside the block
-    int my_e[4], my_rank[4];
-#pragma unroll
-    for (int rd = 0; rd < 4; ++rd) {
-        int c = rd * 4 + w;
-        int t = base + c * WAVE + lane;
-        bool valid = t < T;
-        int e = valid ? idx[t] : 0;
-        valid = valid && e >= 0 && e < E;
-        unsigned long long mask = __ballot(valid);
-        for (int b = 0; b < nbits; ++b) {
-            bool bit = (e >> b) & 1;
-            unsigned long long bal = __ballot(bit);
-            mask &= bit ? bal : ~bal;
-        }
-        int rank = __popcll(mask & ((1ull << lane) - 1ull));
-        if (valid && rank == 0) chunk_cnt[c][e] = (unsigned short)__popcll(mask);
-        my_e[rd] = valid ? e : -1;
-        my_rank[rd] = rank;
-    }
+    if (PPL == 0) rank_chunks();
     __syncthreads();
     for (int e = tid; e < E; e += DSP_THREADS) {
         int run = 0;
@@ -227,8 +240,9 @@ __global__ __launch_bounds__(DSP_THREADS) void dispatch_permute_kernel(
     }
     __syncthreads();
 #pragma unroll
-    for (int rd = 0; rd < 4; ++rd) {
-        int c = rd * 4 + w;
+    for (int rd = 0; rd < RANK_ROUNDS; ++rd) {
+        int c = rd * RANK_WAVES + rank_w;
+        if (rank_w < 0 || c >= DSP_CHUNKS) continue;
         int t = base + c * WAVE + lane;
         int dest = -1;
         int e = my_e[rd];
