@@ -35,14 +35,14 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 PMC_TRAFFIC_BYTES = {
     "cfg1": {"ffn_gemm1": 1.26e6 + 0.52e6, "ffn_gemm2": 1.31e6 + 0.13e6},
     "cfg2": {"ffn_gemm1": 630.59e6 + 15.12e6, "ffn_gemm2": 621.04e6 + 3.78e6},
-    "cfg2k3": {"ffn_gemm1": 696.81e6 + 52.2e6, "ffn_gemm2": 744.65e6 + 13.05e6},
+    "cfg2k3": {"ffn_gemm1": 696.79e6 + 52.2e6, "ffn_gemm2": 744.75e6 + 13.05e6},
     "cfg3": {"ffn_gemm1": 639.41e6 + 24.1e6, "ffn_gemm2": 638.22e6 + 6.02e6},
     "cfg3x": {"ffn_gemm1": 637.84e6 + 23.25e6, "ffn_gemm2": 648.11e6 + 5.81e6},
-    "cfg4": {"ffn_gemm1": 1252.85e6 + 40.63e6, "ffn_gemm2": 1231.42e6 + 10.16e6},
-    "cfg4b": {"ffn_gemm1": 1242.69e6 + 63.36e6, "ffn_gemm2": 1267.12e6 + 15.84e6},
+    "cfg4": {"ffn_gemm1": 1252.87e6 + 40.63e6, "ffn_gemm2": 1231.49e6 + 10.16e6},
+    "cfg4b": {"ffn_gemm1": 1243.81e6 + 63.36e6, "ffn_gemm2": 1266.47e6 + 15.84e6},
     # cfg5: every row goes through the 256 x 256 tile kernel; cfg5stack runs six such layers per step
-    "cfg5": {"ffn_gemm1": 2073.86e6 + 402.65e6, "ffn_gemm2": 2236.31e6 + 100.66e6},
-    "cfg5stack": {"ffn_gemm1": 2073.86e6 + 402.65e6, "ffn_gemm2": 2236.31e6 + 100.66e6},
+    "cfg5": {"ffn_gemm1": 2073.34e6 + 402.65e6, "ffn_gemm2": 2237.45e6 + 100.66e6},
+    "cfg5stack": {"ffn_gemm1": 2073.34e6 + 402.65e6, "ffn_gemm2": 2237.45e6 + 100.66e6},
 }
 
 
